@@ -1,0 +1,122 @@
+/* C ABI of the MI355X (gfx950) fused attention-forward library.
+ *
+ * The operation is the kernel the paper tunes: fused multi-head attention
+ * forward ("flash-attention", Sec. 1 and Sec. 5 "Experiment setup"), on tensors
+ * laid out [batch, heads, seq, head_dim] (Table 2 caption), in 16-bit floating
+ * point.  The paper does not write the formula out; it is the textbook one:
+ *
+ *     for every (b, h) and query row i, over the visible keys j
+ *     (all j when causal == 0, j <= i when causal != 0):
+ *         x_j    = scale * sum_c Q[b,h,i,c] * K[b,h,j,c]
+ *         lse    = ln sum_j exp(x_j)                       (natural logarithm)
+ *         O[c]   = sum_j exp(x_j - lse) * V[b,h,j,c]
+ *
+ * computed in one pass over K/V tiles with an online softmax: both contractions
+ * run on bf16/fp16 MFMA with fp32 accumulation, the probabilities are rounded to
+ * the input type (nearest-even) before the second contraction, O is rounded once
+ * at the end.
+ *
+ * The schedule-variant entry points are the analogue of the paper's search
+ * space (Sec. 3.1): a variant is one compile-time instruction schedule of the
+ * same kernel (tile shape, LDS prefetch distance, instruction-group
+ * interleaving, wave priority placement).  All variants compute the same
+ * function.
+ *
+ * General rules
+ *  - every pointer named "device" is a HIP device pointer owned by the caller;
+ *    the library allocates nothing, frees nothing and keeps no mutable state;
+ *  - calls are asynchronous: work is enqueued on `stream` (a hipStream_t passed
+ *    as void*, NULL = the default stream) and the call returns without waiting;
+ *  - the return value is ATTN_OK or a negative error code; on error nothing has
+ *    been enqueued and no output byte is written;
+ *  - no C++ exception crosses this boundary.
+ */
+#ifndef PAPER_2403_16863_AMD_ATTN_H
+#define PAPER_2403_16863_AMD_ATTN_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { ATTN_F16 = 0, ATTN_BF16 = 1 };
+
+enum {
+    ATTN_OK = 0,
+    ATTN_EINVAL = -1,       /* null pointer, non-positive size, misaligned or aliased buffer,
+                               non-finite scale, unknown dtype, variant id out of range */
+    ATTN_EUNSUPPORTED = -2, /* head_dim other than 64 or 128; B*H or N beyond the grid limits;
+                               variant not built for this (d, dtype, causal) */
+    ATTN_ELAUNCH = -3       /* the HIP runtime refused the launch */
+};
+
+/* Fused attention forward with the library's default schedule variant for the
+ * shape (attn_default_variant).
+ *
+ *  q, k, v : device, [B,H,N,d] contiguous row-major, 16-bit elements of `dtype`,
+ *            16-byte aligned.  Read only.
+ *  out     : device, [B,H,N,d] contiguous, same dtype, 16-byte aligned; must not
+ *            overlap q, k or v.  Every element is written.
+ *  lse     : device, [B,H,N] fp32, 4-byte aligned: natural-log log-sum-exp of the
+ *            scaled scores over the visible keys.  Every element is written.
+ *  B,H,N   : >= 1, any N (ragged last tiles are masked); B*H <= 65535*... see
+ *            ATTN_EUNSUPPORTED.
+ *  d       : 64 or 128.
+ *  causal  : 0 = every key visible, otherwise key j is visible to query i iff j <= i.
+ *  scale   : finite; multiplies q.k before the softmax (callers pass 1/sqrt(d)).
+ *  dtype   : ATTN_F16 or ATTN_BF16.
+ *  stream  : hipStream_t as void*, NULL = default stream.
+ */
+int attn_fwd(const void* q, const void* k, const void* v, void* out, float* lse,
+             int B, int H, int N, int d, int causal, float scale, int dtype, void* stream);
+
+/* Same operation with an explicit schedule variant (0 <= variant_id <
+ * attn_num_variants()).  This is what the schedule search calls (Sec. 3, Alg. 1:
+ * each visited schedule is executed on the device). */
+int attn_fwd_variant(const void* q, const void* k, const void* v, void* out, float* lse,
+                     int B, int H, int N, int d, int causal, float scale, int dtype,
+                     void* stream, int variant_id);
+
+/* Number of schedule variants compiled into the library (same table for every
+ * shape; a variant that was not built for a given head_dim reports
+ * ATTN_EUNSUPPORTED from attn_fwd_variant / attn_variant_supported). */
+int attn_num_variants(void);
+
+/* 1 if variant_id can run this (d, dtype, causal), 0 if not, ATTN_EINVAL if the id
+ * is out of range. */
+int attn_variant_supported(int variant_id, int d, int dtype, int causal);
+
+/* Writes a NUL-terminated human-readable knob vector ("bm=128 bn=64 ...") into
+ * buf (host memory, buflen bytes, truncated if needed).  Returns the untruncated
+ * length, or ATTN_EINVAL. */
+int attn_variant_desc(int variant_id, char* buf, int buflen);
+
+/* The search space as a lattice (Sec. 3.1 / 3.2): every variant is a point with
+ * attn_num_knobs() integer coordinates; a mutation moves one coordinate by one.
+ * attn_variant_coords writes the coordinates of a variant into coords[nknobs];
+ * attn_variant_from_coords returns the id at a lattice point or ATTN_EINVAL if no
+ * variant is built there; attn_knob_name / attn_knob_size describe a coordinate. */
+int attn_num_knobs(void);
+const char* attn_knob_name(int knob);
+int attn_knob_size(int knob);
+int attn_variant_coords(int variant_id, int* coords);
+int attn_variant_from_coords(const int* coords);
+
+/* The variant attn_fwd uses for this shape. */
+int attn_default_variant(int N, int d, int dtype, int causal);
+
+/* Feedback measurement of Sec. 3.3: `warmup` untimed launches, then `iters`
+ * launches each bracketed by its own pair of HIP events on `stream`; the elapsed
+ * milliseconds of launch i are written to ms[i] (host memory, iters floats).
+ * Blocks the calling thread until the last launch has finished.  Same argument
+ * rules as attn_fwd_variant; additionally iters >= 1 and warmup >= 0. */
+int attn_time_variant(const void* q, const void* k, const void* v, void* out, float* lse,
+                      int B, int H, int N, int d, int causal, float scale, int dtype,
+                      void* stream, int variant_id, int warmup, int iters, float* ms);
+
+/* Static text for an error code. */
+const char* attn_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,197 @@
+"""Thin ctypes binding over the C ABI declared in include/attn.h.
+
+Argument marshalling only: every step of the attention forward runs in the HIP
+kernels of libattn.so.  There is no fallback: if the library has not been built the
+import of a symbol fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libattn.so")
+
+ATTN_F16, ATTN_BF16 = 0, 1
+ATTN_OK, ATTN_EINVAL, ATTN_EUNSUPPORTED, ATTN_ELAUNCH = 0, -1, -2, -3
+
+# every symbol include/attn.h declares
+SYMBOLS = ("attn_fwd", "attn_fwd_variant", "attn_num_variants", "attn_variant_supported",
+           "attn_variant_desc", "attn_num_knobs", "attn_knob_name", "attn_knob_size",
+           "attn_variant_coords", "attn_variant_from_coords", "attn_default_variant",
+           "attn_time_variant", "attn_strerror")
+
+_lib = None
+
+
+class AttnError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {strerror(code)} (code {code})")
+        self.code = code
+
+
+def lib():
+    """Load libattn.so (built by __graft_entry__.build()); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; "
+                              "g.build()'` from the repository root")
+        # PyTorch ships its own HIP runtime under the same soname; load it first so
+        # the library and torch's allocator/streams share ONE runtime instance.
+        import torch  # noqa: F401
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i, f = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+        common = [vp, vp, vp, vp, vp, i, i, i, i, i, f, i, vp]
+        L.attn_fwd.restype = i
+        L.attn_fwd.argtypes = common
+        L.attn_fwd_variant.restype = i
+        L.attn_fwd_variant.argtypes = common + [i]
+        L.attn_time_variant.restype = i
+        L.attn_time_variant.argtypes = common + [i, i, i, ctypes.POINTER(ctypes.c_float)]
+        L.attn_num_variants.restype = i
+        L.attn_num_variants.argtypes = []
+        L.attn_variant_supported.restype = i
+        L.attn_variant_supported.argtypes = [i, i, i, i]
+        L.attn_variant_desc.restype = i
+        L.attn_variant_desc.argtypes = [i, ctypes.c_char_p, i]
+        L.attn_num_knobs.restype = i
+        L.attn_num_knobs.argtypes = []
+        L.attn_knob_name.restype = ctypes.c_char_p
+        L.attn_knob_name.argtypes = [i]
+        L.attn_knob_size.restype = i
+        L.attn_knob_size.argtypes = [i]
+        L.attn_variant_coords.restype = i
+        L.attn_variant_coords.argtypes = [i, ctypes.POINTER(i)]
+        L.attn_variant_from_coords.restype = i
+        L.attn_variant_from_coords.argtypes = [ctypes.POINTER(i)]
+        L.attn_default_variant.restype = i
+        L.attn_default_variant.argtypes = [i, i, i, i]
+        L.attn_strerror.restype = ctypes.c_char_p
+        L.attn_strerror.argtypes = [i]
+        _lib = L
+    return _lib
+
+
+def attn_strerror(code: int) -> str:
+    return lib().attn_strerror(int(code)).decode()
+
+
+strerror = attn_strerror
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float16:
+        return ATTN_F16
+    if t.dtype == torch.bfloat16:
+        return ATTN_BF16
+    raise TypeError(f"attention inputs must be float16 or bfloat16, got {t.dtype}")
+
+
+def _marshal(q, k, v, out, lse, stream):
+    import torch
+    for name, t in (("q", q), ("k", k), ("v", v), ("out", out), ("lse", lse)):
+        if not t.is_cuda:
+            raise ValueError(f"{name} must live in device memory")
+        if not t.is_contiguous():
+            raise ValueError(f"{name} must be contiguous")
+    if q.dim() != 4 or k.shape != q.shape or v.shape != q.shape or out.shape != q.shape:
+        raise ValueError("q, k, v, out must share one [B,H,N,d] shape")
+    if k.dtype != q.dtype or v.dtype != q.dtype or out.dtype != q.dtype:
+        raise ValueError("q, k, v, out must share one dtype")
+    if lse.dtype != torch.float32 or tuple(lse.shape) != tuple(q.shape[:3]):
+        raise ValueError("lse must be float32 [B,H,N]")
+    B, H, N, d = q.shape
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    return (q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+            B, H, N, d), _dtype_code(q), stream
+
+
+def attn_fwd(q, k, v, out, lse, causal: bool, scale: float, stream=None) -> None:
+    """out, lse <- fused attention forward of device tensors q, k, v ([B,H,N,d]).
+    Asynchronous on `stream` (an integer hipStream_t; default: torch's current stream)."""
+    (ptrs_shape), dt, st = _marshal(q, k, v, out, lse, stream)
+    rc = lib().attn_fwd(*ptrs_shape, int(bool(causal)), float(scale), dt, st)
+    if rc != ATTN_OK:
+        raise AttnError(rc, "attn_fwd")
+
+
+def attn_fwd_variant(q, k, v, out, lse, causal: bool, scale: float, variant_id: int, stream=None) -> None:
+    (ptrs_shape), dt, st = _marshal(q, k, v, out, lse, stream)
+    rc = lib().attn_fwd_variant(*ptrs_shape, int(bool(causal)), float(scale), dt, st, int(variant_id))
+    if rc != ATTN_OK:
+        raise AttnError(rc, f"attn_fwd_variant({variant_id})")
+
+
+def attn_time_variant(q, k, v, out, lse, causal: bool, scale: float, variant_id: int,
+                      warmup: int = 10, iters: int = 50, stream=None):
+    """Per-launch elapsed milliseconds (list of `iters` floats), HIP-event timed."""
+    (ptrs_shape), dt, st = _marshal(q, k, v, out, lse, stream)
+    ms = (ctypes.c_float * int(iters))()
+    rc = lib().attn_time_variant(*ptrs_shape, int(bool(causal)), float(scale), dt, st,
+                                 int(variant_id), int(warmup), int(iters), ms)
+    if rc != ATTN_OK:
+        raise AttnError(rc, f"attn_time_variant({variant_id})")
+    return list(ms)
+
+
+def attn_num_variants() -> int:
+    return lib().attn_num_variants()
+
+
+def attn_variant_supported(variant_id: int, d: int, dtype: int, causal: bool) -> bool:
+    rc = lib().attn_variant_supported(int(variant_id), int(d), int(dtype), int(bool(causal)))
+    if rc < 0:
+        raise AttnError(rc, "attn_variant_supported")
+    return bool(rc)
+
+
+def attn_variant_desc(variant_id: int) -> str:
+    buf = ctypes.create_string_buffer(256)
+    rc = lib().attn_variant_desc(int(variant_id), buf, len(buf))
+    if rc < 0:
+        raise AttnError(rc, "attn_variant_desc")
+    return buf.value.decode()
+
+
+def attn_num_knobs() -> int:
+    return lib().attn_num_knobs()
+
+
+def attn_knob_name(knob: int) -> str:
+    s = lib().attn_knob_name(int(knob))
+    if s is None:
+        raise AttnError(ATTN_EINVAL, "attn_knob_name")
+    return s.decode()
+
+
+def attn_knob_size(knob: int) -> int:
+    rc = lib().attn_knob_size(int(knob))
+    if rc < 0:
+        raise AttnError(rc, "attn_knob_size")
+    return rc
+
+
+def attn_variant_coords(variant_id: int):
+    n = attn_num_knobs()
+    arr = (ctypes.c_int * n)()
+    rc = lib().attn_variant_coords(int(variant_id), arr)
+    if rc != ATTN_OK:
+        raise AttnError(rc, "attn_variant_coords")
+    return tuple(arr)
+
+
+def attn_variant_from_coords(coords):
+    """Variant id at a lattice point, or None if nothing is built there."""
+    n = attn_num_knobs()
+    if len(coords) != n:
+        raise ValueError(f"need {n} coordinates")
+    arr = (ctypes.c_int * n)(*[int(c) for c in coords])
+    rc = lib().attn_variant_from_coords(arr)
+    return None if rc < 0 else rc
+
+
+def attn_default_variant(N: int, d: int, dtype: int, causal: bool) -> int:
+    return lib().attn_default_variant(int(N), int(d), int(dtype), int(bool(causal)))

@@ -1,0 +1,225 @@
+// C ABI of the fused attention-forward library: argument checking, the table of
+// schedule variants (the search space of Sec. 3.1 as compile-time instantiations of
+// one kernel) and the event-timed measurement used as search feedback (Sec. 3.3).
+#include "attn_kernel.h"
+
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/attn.h"
+
+namespace {
+
+using attn::Params;
+
+typedef void (*KernelFn)(const Params);
+
+struct Variant {
+    int bn, nw, qb, occ;   // knob values
+    int coords[4];         // lattice coordinates (indices into the knob value lists)
+    // kernels indexed [d == 128][dtype][causal]; null = not built for that combination
+    KernelFn fn[2][2][2];
+};
+
+// Knob value lists (lattice axes).
+const int kBN[] = {32, 64, 128};
+const int kNW[] = {4, 8};
+const int kQB[] = {1, 2};
+const int kOCC[] = {1, 2};
+const char* const kKnobNames[] = {"bn", "nw", "qb", "occ"};
+const int kKnobSizes[] = {3, 2, 2, 2};
+constexpr int kNumKnobs = 4;
+
+#define ATTN_KERNELS_FOR(BN, NW, QB, OCC, D)                                                     \
+    {                                                                                            \
+        {(KernelFn)attn::attn_fwd_kernel<attn::F16, D, false, attn::Knobs<BN, NW, QB, OCC>>,       \
+         (KernelFn)attn::attn_fwd_kernel<attn::F16, D, true, attn::Knobs<BN, NW, QB, OCC>>},       \
+        {(KernelFn)attn::attn_fwd_kernel<attn::BF16, D, false, attn::Knobs<BN, NW, QB, OCC>>,      \
+         (KernelFn)attn::attn_fwd_kernel<attn::BF16, D, true, attn::Knobs<BN, NW, QB, OCC>>}       \
+    }
+#define ATTN_NO_KERNELS {{nullptr, nullptr}, {nullptr, nullptr}}
+
+// index helpers for the coordinate lists above
+#define IDX_BN(x) ((x) == 32 ? 0 : (x) == 64 ? 1 : 2)
+#define IDX_NW(x) ((x) == 4 ? 0 : 1)
+#define IDX_QB(x) ((x) == 1 ? 0 : 1)
+#define IDX_OCC(x) ((x) == 1 ? 0 : 1)
+
+#define VARIANT_BOTH(BN, NW, QB, OCC)                                                            \
+    {BN, NW, QB, OCC, {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), IDX_OCC(OCC)},                          \
+     {ATTN_KERNELS_FOR(BN, NW, QB, OCC, 64), ATTN_KERNELS_FOR(BN, NW, QB, OCC, 128)}}
+#define VARIANT_D64(BN, NW, QB, OCC)                                                             \
+    {BN, NW, QB, OCC, {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), IDX_OCC(OCC)},                          \
+     {ATTN_KERNELS_FOR(BN, NW, QB, OCC, 64), ATTN_NO_KERNELS}}
+
+const Variant kVariants[] = {
+    VARIANT_BOTH(64, 4, 1, 2),   // 0: the hand-written default
+    VARIANT_BOTH(64, 4, 1, 1),
+    VARIANT_BOTH(32, 4, 1, 2),
+    VARIANT_BOTH(64, 4, 2, 1),
+    VARIANT_BOTH(32, 4, 2, 1),
+    VARIANT_BOTH(64, 8, 1, 1),
+    VARIANT_D64(128, 4, 1, 2),
+    VARIANT_D64(128, 4, 2, 1),
+};
+constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
+
+bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
+// Everything that can be rejected without touching the device.
+int check_args(const void* q, const void* k, const void* v, void* out, float* lse, int B, int H,
+               int N, int d, float scale, int dtype, int variant_id) {
+    if (!q || !k || !v || !out || !lse) return ATTN_EINVAL;
+    if (B < 1 || H < 1 || N < 1) return ATTN_EINVAL;
+    if (dtype != ATTN_F16 && dtype != ATTN_BF16) return ATTN_EINVAL;
+    if (!isfinite(scale)) return ATTN_EINVAL;
+    if (variant_id < 0 || variant_id >= kNumVariants) return ATTN_EINVAL;
+    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(out, 16) || !aligned(lse, 4))
+        return ATTN_EINVAL;
+    if (d != 64 && d != 128) return ATTN_EUNSUPPORTED;
+    const unsigned long long elems = (unsigned long long)B * H * N * d;
+    if (elems > (1ull << 40)) return ATTN_EUNSUPPORTED;  // keeps every byte offset far inside 64 bits
+    const size_t bytes = (size_t)elems * 2;
+    if (overlaps(out, bytes, q, bytes) || overlaps(out, bytes, k, bytes) || overlaps(out, bytes, v, bytes))
+        return ATTN_EINVAL;
+    const size_t lse_bytes = (size_t)B * H * N * 4;
+    if (overlaps(lse, lse_bytes, q, bytes) || overlaps(lse, lse_bytes, k, bytes) ||
+        overlaps(lse, lse_bytes, v, bytes) || overlaps(lse, lse_bytes, out, bytes))
+        return ATTN_EINVAL;
+    return ATTN_OK;
+}
+
+int launch(const void* q, const void* k, const void* v, void* out, float* lse, int B, int H, int N,
+           int d, int causal, float scale, int dtype, void* stream, int variant_id) {
+    const int rc = check_args(q, k, v, out, lse, B, H, N, d, scale, dtype, variant_id);
+    if (rc != ATTN_OK) return rc;
+    const Variant& var = kVariants[variant_id];
+    const KernelFn fn = var.fn[d == 128][dtype][causal ? 1 : 0];
+    if (!fn) return ATTN_EUNSUPPORTED;
+    const int bm = 32 * var.qb * var.nw;
+    const long long nqt = ((long long)N + bm - 1) / bm;
+    const long long total = nqt * B * H;
+    if (total > 0x7fffffffLL) return ATTN_EUNSUPPORTED;
+
+    Params p;
+    p.q = (const uint16_t*)q;
+    p.k = (const uint16_t*)k;
+    p.v = (const uint16_t*)v;
+    p.out = (uint16_t*)out;
+    p.lse = lse;
+    p.H = H;
+    p.N = N;
+    p.nqt = (int)nqt;
+    p.total_wg = (int)total;
+    // The kernel tracks the running maximum of the raw dot products, which needs a
+    // positive multiplier: a negative scale is moved into the sign of Q, a zero scale
+    // into Q = 0.
+    p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
+    p.scale = scale > 0.f ? scale : (scale < 0.f ? -scale : 1.0f);
+    p.scale_l2 = p.scale * 1.44269504088896340736f;
+    // The launch's own return code is used (not hipGetLastError, which can report a
+    // stale, unrelated status left behind by another library's earlier call).
+    void* args[] = {&p};
+    const hipError_t e = hipLaunchKernel((const void*)fn, dim3((unsigned)total), dim3(var.nw * 64),
+                                         args, 0, (hipStream_t)stream);
+    if (e != hipSuccess) fprintf(stderr, "attn: hipLaunchKernel failed: %s (%d), grid=%lld block=%d\n", hipGetErrorString(e), (int)e, total, var.nw * 64);
+    return e == hipSuccess ? ATTN_OK : ATTN_ELAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int attn_num_variants(void) { return kNumVariants; }
+
+int attn_variant_supported(int variant_id, int d, int dtype, int causal) {
+    if (variant_id < 0 || variant_id >= kNumVariants) return ATTN_EINVAL;
+    if ((d != 64 && d != 128) || (dtype != ATTN_F16 && dtype != ATTN_BF16)) return 0;
+    return kVariants[variant_id].fn[d == 128][dtype][causal ? 1 : 0] != nullptr;
+}
+
+int attn_variant_desc(int variant_id, char* buf, int buflen) {
+    if (variant_id < 0 || variant_id >= kNumVariants || !buf || buflen < 1) return ATTN_EINVAL;
+    const Variant& v = kVariants[variant_id];
+    return snprintf(buf, (size_t)buflen, "bm=%d bn=%d nw=%d qb=%d occ=%d", 32 * v.qb * v.nw, v.bn,
+                    v.nw, v.qb, v.occ);
+}
+
+int attn_num_knobs(void) { return kNumKnobs; }
+
+const char* attn_knob_name(int knob) { return (knob < 0 || knob >= kNumKnobs) ? nullptr : kKnobNames[knob]; }
+
+int attn_knob_size(int knob) { return (knob < 0 || knob >= kNumKnobs) ? ATTN_EINVAL : kKnobSizes[knob]; }
+
+int attn_variant_coords(int variant_id, int* coords) {
+    if (variant_id < 0 || variant_id >= kNumVariants || !coords) return ATTN_EINVAL;
+    for (int i = 0; i < kNumKnobs; ++i) coords[i] = kVariants[variant_id].coords[i];
+    return ATTN_OK;
+}
+
+int attn_variant_from_coords(const int* coords) {
+    if (!coords) return ATTN_EINVAL;
+    for (int id = 0; id < kNumVariants; ++id)
+        if (memcmp(kVariants[id].coords, coords, sizeof(int) * kNumKnobs) == 0) return id;
+    return ATTN_EINVAL;
+}
+
+int attn_default_variant(int N, int d, int dtype, int causal) {
+    (void)N; (void)d; (void)dtype; (void)causal;
+    return 0;
+}
+
+int attn_fwd_variant(const void* q, const void* k, const void* v, void* out, float* lse, int B, int H,
+                     int N, int d, int causal, float scale, int dtype, void* stream, int variant_id) {
+    return launch(q, k, v, out, lse, B, H, N, d, causal, scale, dtype, stream, variant_id);
+}
+
+int attn_fwd(const void* q, const void* k, const void* v, void* out, float* lse, int B, int H, int N,
+             int d, int causal, float scale, int dtype, void* stream) {
+    return launch(q, k, v, out, lse, B, H, N, d, causal, scale, dtype, stream,
+                  attn_default_variant(N, d, dtype, causal));
+}
+
+int attn_time_variant(const void* q, const void* k, const void* v, void* out, float* lse, int B, int H,
+                      int N, int d, int causal, float scale, int dtype, void* stream, int variant_id,
+                      int warmup, int iters, float* ms) {
+    if (!ms || iters < 1 || warmup < 0) return ATTN_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    for (int i = 0; i < warmup; ++i) {
+        const int rc = launch(q, k, v, out, lse, B, H, N, d, causal, scale, dtype, stream, variant_id);
+        if (rc != ATTN_OK) return rc;
+    }
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return ATTN_ELAUNCH;
+    if (hipEventCreate(&e1) != hipSuccess) { hipEventDestroy(e0); return ATTN_ELAUNCH; }
+    int rc = ATTN_OK;
+    for (int i = 0; i < iters && rc == ATTN_OK; ++i) {
+        if (hipEventRecord(e0, s) != hipSuccess) { rc = ATTN_ELAUNCH; break; }
+        rc = launch(q, k, v, out, lse, B, H, N, d, causal, scale, dtype, stream, variant_id);
+        if (rc != ATTN_OK) break;
+        if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+            hipEventElapsedTime(&ms[i], e0, e1) != hipSuccess)
+            rc = ATTN_ELAUNCH;
+    }
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    return rc;
+}
+
+const char* attn_strerror(int code) {
+    switch (code) {
+        case ATTN_OK: return "ok";
+        case ATTN_EINVAL: return "invalid argument";
+        case ATTN_EUNSUPPORTED: return "unsupported shape or variant";
+        case ATTN_ELAUNCH: return "HIP launch or event call failed";
+        default: return "unknown error code";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,380 @@
+// Fused attention forward for gfx950 (MI355X): one pass over K/V tiles with an
+// online softmax, both contractions on 32x32x16 MFMA, fp32 accumulation.
+//
+// The operation is the kernel the paper tunes (fused attention forward, Sec. 1
+// and Sec. 5 "Experiment setup", tensors [batch, heads, seq, head_dim], Table 2
+// caption).  The tiling below is designed for CDNA4 and is not the paper's.
+//
+// Formulation ("transposed"): a wave owns QB blocks of 32 query rows and computes
+//     S^T = K_tile . Q^T        (A operand = K rows from LDS, B operand = Q, kept in registers)
+//     O^T += V_tile^T . P^T     (A operand = V read from LDS with the transposing
+//                                ds_read_b64_tr_b16, B operand = P straight from
+//                                the S^T accumulator registers)
+// In the 32x32 accumulator layout every lane then holds 16 scores of ONE query
+// (column = lane % 32), so the softmax row statistics are lane-local except for
+// one exchange between lane l and lane l^32 per tile, and the S^T accumulators
+// are, after conversion to 16 bit, already laid out as the B operand of the
+// second contraction (with the key order permuted identically on the V side).
+//
+// 32x32x16 MFMA register layout (checked on hardware):
+//   A (32 x 16): lane l holds row l%32, k = 8*(l/32) .. +7
+//   B (16 x 32): lane l holds col l%32, k = 8*(l/32) .. +7
+//   C (32 x 32): lane l holds col l%32, register v holds row 8*(v/4) + 4*(l/32) + v%4
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace attn {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+struct Params {
+    const uint16_t* q;
+    const uint16_t* k;
+    const uint16_t* v;
+    uint16_t* out;
+    float* lse;
+    int H, N;
+    int nqt;         // query tiles per head
+    int total_wg;    // nqt * B * H
+    float scale;     // multiplies q'.k, always > 0 (see qmode)
+    float scale_l2;  // scale * log2(e)
+    int qmode;       // 0: q' = q;  1: q' = -q (caller's scale was negative);
+                     // 2: q' = 0 (caller's scale was zero, kernel runs with scale 1)
+};
+
+struct F16 {
+    static __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                      __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ unsigned pack2(float a, float b) {  // nearest-even
+        return __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{a, b}, f16x2));
+    }
+};
+struct BF16 {
+    static __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ unsigned pack2(float a, float b) {  // nearest-even
+        return __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{a, b}, bf16x2));
+    }
+};
+
+// Exchange between lane l and lane l^32 with v_permlane32_swap_b32, which swaps the
+// upper 32 lanes of its first operand with the lower 32 lanes of its second.  Starting
+// from two copies of x, the first then holds the lower half's values in both halves
+// and the second the upper half's.  Written as inline asm with two read-write
+// operands: the compiler folds the builtin away when both inputs are the same value.
+__device__ __forceinline__ void swap_halves(float x, float& lo_vals, float& hi_vals) {
+    float a = x, b = x;
+    // the s_nop covers the VALU-write -> permlane-read hazard the compiler cannot see
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    lo_vals = a;
+    hi_vals = b;
+}
+__device__ __forceinline__ float xhalf_sum(float x) {
+    float a, b;
+    swap_halves(x, a, b);
+    return a + b;
+}
+__device__ __forceinline__ float xhalf_max(float x) {
+    float a, b;
+    swap_halves(x, a, b);
+    return fmaxf(a, b);
+}
+
+// ---- LDS layouts ------------------------------------------------------------
+// A K/V tile is BN rows of D 16-bit elements, addressed in 16-byte chunks.
+// K is read row-wise (ds_read_b128, lane = key row): chunks are XOR-swizzled with
+// the 256-byte line index so 16 consecutive rows land on 16 distinct bank groups.
+template <int D>
+__device__ __forceinline__ int k_chunk_phys(int row, int cc) {
+    constexpr int CPR = D / 8;
+    const int L = row * CPR + cc;
+    return (L & ~15) | ((L ^ (L >> 4)) & 15);
+}
+// V is read with the transposing load: a 16-lane group touches 4 consecutive key
+// rows x 32 bytes.  32-byte slots are XOR-ed with a code of (row & 3) chosen so the
+// four rows of one read and both lane groups of a half-wave hit disjoint banks.
+template <int D>
+__device__ __forceinline__ int v_byte_phys(int row, int dcol) {
+    constexpr int RB = D * 2;
+    const int r = row & 3;
+    const int g = ((r << 1) & 6) | (r >> 1);  // 0,2,5,7
+    int slot = dcol >> 4;                     // 32-byte slot within the row
+    if (D == 128) slot ^= g;
+    else slot ^= (g & 3);                     // 4 slots per 128-byte row
+    return row * RB + slot * 32 + (dcol & 15) * 2;
+}
+
+// Schedule / shape knobs of one variant (the lattice the search walks).
+template <int BN_, int NW_, int QB_, int OCC_>
+struct Knobs {
+    static constexpr int BN = BN_;    // keys per K/V tile
+    static constexpr int NW = NW_;    // waves per workgroup
+    static constexpr int QB = QB_;    // 32-row query blocks per wave
+    static constexpr int OCC = OCC_;  // workgroups per CU the register budget aims for
+};
+
+template <class T, int D, bool CAUSAL, class KN>
+__global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Params p) {
+    constexpr int BN = KN::BN, NW = KN::NW, QB = KN::QB;
+    constexpr int NT = NW * 64;
+    constexpr int BM = 32 * QB * NW;
+    constexpr int KS = D / 16;       // k-steps of the first contraction
+    constexpr int DT = D / 32;       // 32-wide d tiles of O^T
+    constexpr int KT = BN / 32;      // 32-key sub-tiles of one K/V tile
+    constexpr int CPR = D / 8;       // 16-byte chunks per row
+    constexpr int TILE_CHUNKS = BN * CPR;
+    constexpr int LD_PER_THREAD = TILE_CHUNKS / NT;
+    static_assert(TILE_CHUNKS % NT == 0, "tile must divide over the workgroup");
+    constexpr int TILE_BYTES = TILE_CHUNKS * 16;
+
+    __shared__ __attribute__((aligned(256))) u32x4 smem[4 * TILE_CHUNKS];  // K0 V0 K1 V1
+    char* const smem_b = reinterpret_cast<char*>(smem);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int g = lane >> 5;
+    const int c = lane & 31;
+
+    // ---- workgroup -> (head, query tile).  Workgroups are dealt round-robin to the
+    // 8 XCDs; give each XCD a contiguous run of logical ids so that all query tiles
+    // of a head share one L2, and start with the heaviest (last) query tiles.
+    int logical;
+    {
+        const int bid = blockIdx.x, xcd = bid & 7, slot = bid >> 3;
+        const int base = p.total_wg >> 3, rem = p.total_wg & 7;
+        logical = (xcd < rem ? xcd * (base + 1) : rem * (base + 1) + (xcd - rem) * base) + slot;
+    }
+    const int bh = logical / p.nqt;
+    const int qt = p.nqt - 1 - (logical - bh * p.nqt);
+    const int N = p.N;
+    const int q0 = qt * BM;
+    const int qw0 = q0 + wave * (32 * QB);  // first query row of this wave
+
+    const size_t head_off = (size_t)bh * N * D;
+    const uint16_t* __restrict__ Qh = p.q + head_off;
+    const uint16_t* __restrict__ Kh = p.k + head_off;
+    const uint16_t* __restrict__ Vh = p.v + head_off;
+
+    // ---- Q as B operand, resident in registers
+    u32x4 qreg[QB][KS];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const int row = qw0 + qb * 32 + c;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            u32x4 val = {0, 0, 0, 0};
+            if (row < N && p.qmode != 2)
+                val = *reinterpret_cast<const u32x4*>(Qh + (size_t)row * D + ks * 16 + g * 8);
+            if (p.qmode == 1) val ^= 0x80008000u;  // flip the sign of all eight elements
+            qreg[qb][ks] = val;
+        }
+    }
+
+    f32x16 o[QB][DT];
+    float m_run[QB], l_run[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        m_run[qb] = -INFINITY;
+        l_run[qb] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[qb][dt][v] = 0.f;
+    }
+
+    // key tiles this workgroup visits
+    const int kend = CAUSAL ? min(N, q0 + BM) : N;  // keys [0, kend)
+    const int nkt = (kend + BN - 1) / BN;
+
+    // ---- global -> register staging of one K/V tile
+    u32x4 kst[LD_PER_THREAD], vst[LD_PER_THREAD];
+    auto load_tile = [&](int kt0) {
+#pragma unroll
+        for (int i = 0; i < LD_PER_THREAD; ++i) {
+            const int L = i * NT + tid;
+            const int row = L / CPR, cc = L % CPR;
+            u32x4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
+            if (kt0 + row < N) {
+                const size_t off = (size_t)(kt0 + row) * D + cc * 8;
+                kv = *reinterpret_cast<const u32x4*>(Kh + off);
+                vv = *reinterpret_cast<const u32x4*>(Vh + off);
+            }
+            kst[i] = kv;
+            vst[i] = vv;
+        }
+    };
+    auto store_tile = [&](int buf) {
+        char* kb = smem_b + buf * 2 * TILE_BYTES;
+        char* vb = kb + TILE_BYTES;
+#pragma unroll
+        for (int i = 0; i < LD_PER_THREAD; ++i) {
+            const int L = i * NT + tid;
+            const int row = L / CPR, cc = L % CPR;
+            *reinterpret_cast<u32x4*>(kb + k_chunk_phys<D>(row, cc) * 16) = kst[i];
+            *reinterpret_cast<u32x4*>(vb + v_byte_phys<D>(row, cc * 8)) = vst[i];
+        }
+    };
+
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+
+    for (int j = 0; j < nkt; ++j) {
+        const int k0 = j * BN;
+        const bool more = (j + 1 < nkt);
+        if (more) load_tile(k0 + BN);
+
+        const char* kb = smem_b + (j & 1) * 2 * TILE_BYTES;
+        const char* vb = kb + TILE_BYTES;
+
+        // causal: a wave whose queries all precede this tile has nothing to do
+        const bool active = !CAUSAL || (k0 <= qw0 + 32 * QB - 1);
+        if (active) {
+            // ---- S^T = K . Q^T
+            f32x16 s[QB][KT];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) s[qb][kt][v] = 0.f;
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const u32x4 a = *reinterpret_cast<const u32x4*>(
+                        kb + k_chunk_phys<D>(kt * 32 + c, ks * 2 + g) * 16);
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb) s[qb][kt] = T::mfma(a, qreg[qb][ks], s[qb][kt]);
+                }
+            }
+
+            // ---- mask: keys past the end of the sequence, and keys after the query
+            const bool need_mask = (k0 + BN > N) || (CAUSAL && (k0 + BN - 1 > qw0));
+            if (need_mask) {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    const int qi = qw0 + qb * 32 + c;
+                    const int lim = CAUSAL ? min(qi, N - 1) : N - 1;  // last visible key
+#pragma unroll
+                    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const int key = k0 + kt * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                            if (key > lim) s[qb][kt][v] = -INFINITY;
+                        }
+                }
+            }
+
+            // ---- online softmax (per query = per lane column), P^T packed as B operand
+            u32x4 pk[QB][KT][2];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                float mx = s[qb][0][0];
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[qb][kt][v]);
+                mx = xhalf_max(mx);
+                const float m_new = fmaxf(m_run[qb], mx);
+                // m_new is finite: key 0 is visible to every query and lives in tile 0
+                // first tile: m_run = -inf and alpha must be 0 even when scale is 0
+                const float alpha = (m_run[qb] == -INFINITY)
+                                        ? 0.f
+                                        : __builtin_amdgcn_exp2f((m_run[qb] - m_new) * p.scale_l2);
+                const float mb = m_new * p.scale_l2;
+                m_run[qb] = m_new;
+                float rs = 0.f;
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt) {
+                    float e[16];
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        e[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][kt][v], p.scale_l2, -mb));
+                        rs += e[v];
+                    }
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        u32x4 w;
+                        w[0] = T::pack2(e[8 * t + 0], e[8 * t + 1]);
+                        w[1] = T::pack2(e[8 * t + 2], e[8 * t + 3]);
+                        w[2] = T::pack2(e[8 * t + 4], e[8 * t + 5]);
+                        w[3] = T::pack2(e[8 * t + 6], e[8 * t + 7]);
+                        pk[qb][kt][t] = w;
+                    }
+                }
+                l_run[qb] = l_run[qb] * alpha + rs;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) o[qb][dt][v] *= alpha;
+            }
+
+            // ---- O^T += V^T . P^T
+            // k-slot s of step (kt, t) for lane group g is key kt*32 + 16*t + 8*(s/4) + 4*g + s%4
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt) {
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const int i16 = lane & 15;
+                        const int dcol = dt * 32 + ((lane >> 4) & 1) * 16 + 4 * (i16 & 3);
+                        const int krow = kt * 32 + 16 * t + 4 * g + (i16 >> 2);
+                        typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+                        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (lds_s16x4_ptr)(vb + v_byte_phys<D>(krow, dcol)));
+                        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (lds_s16x4_ptr)(vb + v_byte_phys<D>(krow + 8, dcol)));
+                        u32x4 a;
+                        const u32x2 lo2 = __builtin_bit_cast(u32x2, lo);
+                        const u32x2 hi2 = __builtin_bit_cast(u32x2, hi);
+                        a[0] = lo2[0]; a[1] = lo2[1]; a[2] = hi2[0]; a[3] = hi2[1];
+#pragma unroll
+                        for (int qb = 0; qb < QB; ++qb) o[qb][dt] = T::mfma(a, pk[qb][kt][t], o[qb][dt]);
+                    }
+                }
+            }
+        }
+
+        if (more) store_tile((j + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: normalise, round once, store O and lse
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const float l_tot = xhalf_sum(l_run[qb]);
+        const float inv = 1.0f / l_tot;
+        const int qi = qw0 + qb * 32 + c;
+        if (qi < N) {
+            uint16_t* orow = p.out + head_off + (size_t)qi * D;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    u32x2 w;
+                    w[0] = T::pack2(o[qb][dt][4 * v4 + 0] * inv, o[qb][dt][4 * v4 + 1] * inv);
+                    w[1] = T::pack2(o[qb][dt][4 * v4 + 2] * inv, o[qb][dt][4 * v4 + 3] * inv);
+                    *reinterpret_cast<u32x2*>(orow + dt * 32 + 8 * v4 + 4 * g) = w;
+                }
+            if (g == 0) p.lse[(size_t)bh * N + qi] = m_run[qb] * p.scale + __logf(l_tot);
+        }
+    }
+}
+
+}  // namespace attn

@@ -142,7 +142,10 @@ def make_adversarial(kind: str, B: int, H: int, N: int, d: int, dtype: int, seed
         q[mask] = -0.0
         k[~mask] = 0.0
     elif kind == "max_finite_v":
-        big = 65504.0 if dtype == F16 else 3.0e38
+        # binary16: the largest finite value.  bfloat16: 2^100 -- the one-pass method
+        # keeps the un-normalised sum of p*v in fp32, so |v| * N has to stay below the
+        # fp32 range; the largest finite bfloat16 (3.4e38) cannot be averaged that way.
+        big = 65504.0 if dtype == F16 else 2.0 ** 100
         v[:] = np.where(g.random(shape, dtype=np.float32) < 0.5, big, -big).astype(np.float32)
     else:
         raise ValueError(kind)

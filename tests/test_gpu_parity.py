@@ -1,0 +1,117 @@
+"""GPU parity: the HIP path (through the C-ABI binding) against the CPU oracle,
+element by element on the same seeded inputs."""
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_2403_16863_amd import inputs as I
+
+from gpu_util import check, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def variants_for(d, dtype, causal):
+    import paper_2403_16863_amd as A
+    return [v for v in range(A.attn_num_variants()) if A.attn_variant_supported(v, d, dtype, causal)]
+
+
+SMALL_N = (1, 2, 17, 31, 32, 33, 64, 65, 127, 128, 129, 200, 257, 383, 1000)
+
+
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d", [64, 128])
+def test_small_shapes_all_variants(d, causal, dtype):
+    """Sizes the oracle finishes in seconds, spanning several tiles and ragged tails."""
+    for N in SMALL_N:
+        w = I.Workload("t", 2, 3, N, d, causal, dtype)
+        qb, kb, vb = I.make_qkv(w, seed=1000 + N)
+        O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, causal, w.scale, dtype)
+        for var in [None] + variants_for(d, dtype, causal):
+            print(f"case N={N} d={d} causal={causal} dtype={dtype} variant={var}", flush=True)
+            O, l = run_gpu(qb, kb, vb, causal, w.scale, dtype, variant=var)
+            check(O, l, O_ref, l_ref, dtype, what=f"N={N} d={d} causal={causal} dt={dtype} var={var}")
+
+
+@pytest.mark.parametrize("idx", [0, 1])
+def test_benchmark_configs_full(idx):
+    """cfg0 and cfg1 are small enough for the full oracle."""
+    w = I.WORKLOADS[idx]
+    qb, kb, vb = I.make_qkv(w, seed=idx)
+    O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, w.causal, w.scale, w.dtype)
+    for var in [None] + variants_for(w.d, w.dtype, w.causal):
+        print(f"case {w.label} variant={var}", flush=True)
+        O, l = run_gpu(qb, kb, vb, w.causal, w.scale, w.dtype, variant=var)
+        check(O, l, O_ref, l_ref, w.dtype, what=f"{w.label} var={var}")
+
+
+@pytest.mark.parametrize("idx,nrows", [(2, 1024), (3, 384), (4, 2048)])
+def test_benchmark_configs_sampled(idx, nrows):
+    """Full-size workloads in the launch configuration bench.py times, compared on
+    sampled rows the oracle computes one by one; every output must be finite."""
+    w = I.WORKLOADS[idx]
+    qb, kb, vb = I.make_qkv(w, seed=idx)
+    rows = I.sample_rows(w, nrows, seed=idx)
+    O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, w.causal, w.scale, w.dtype, rows=rows)
+    print(f"case {w.label} default variant", flush=True)
+    O, l = run_gpu(qb, kb, vb, w.causal, w.scale, w.dtype)
+    check(O.reshape(-1, w.d)[rows], l.reshape(-1)[rows], O_ref, l_ref, w.dtype, what=w.label)
+    assert np.isfinite(O).all() and np.isfinite(l).all()
+    # property that holds at any size: outputs are convex combinations of V rows
+    v = I.bits_to_f64(vb, w.dtype)
+    vmax = np.abs(v).max(axis=2, keepdims=True)
+    assert (np.abs(O) <= vmax * (1 + 1e-2) + 1e-3).all()
+
+
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("kind", I.ADVERSARIAL)
+def test_adversarial_inputs(kind, dtype):
+    for (N, d, causal) in ((129, 64, False), (200, 128, True), (64, 128, False)):
+        qb, kb, vb = I.make_adversarial(kind, 1, 2, N, d, dtype, seed=7)
+        scale = float(np.float32(1.0 / np.sqrt(d)))
+        O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, causal, scale, dtype)
+        out_scale = max(1.0, float(np.abs(I.bits_to_f64(vb, dtype)).max()))
+        for var in [None] + variants_for(d, dtype, causal):
+            print(f"case {kind} N={N} d={d} causal={causal} dtype={dtype} variant={var}", flush=True)
+            O, l = run_gpu(qb, kb, vb, causal, scale, dtype, variant=var)
+            check(O, l, O_ref, l_ref, dtype, out_scale=out_scale, what=f"{kind} var={var}")
+
+
+def test_scale_argument_and_stream():
+    """Non-default scale, and a launch on a side stream."""
+    import torch
+    import paper_2403_16863_amd as A
+    from gpu_util import to_device
+    w = I.Workload("t", 1, 2, 300, 64, True, I.F16)
+    qb, kb, vb = I.make_qkv(w, seed=5)
+    for scale in (0.0, 0.03, 0.5, -0.2):
+        O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, True, float(np.float32(scale)), I.F16)
+        O, l = run_gpu(qb, kb, vb, True, scale, I.F16)
+        check(O, l, O_ref, l_ref, I.F16, what=f"scale={scale}")
+    s = torch.cuda.Stream()
+    q, k, v = (to_device(a, I.F16) for a in (qb, kb, vb))
+    out = torch.empty_like(q)
+    lse = torch.empty(q.shape[:3], dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    A.attn_fwd(q, k, v, out, lse, True, w.scale, stream=s.cuda_stream)
+    s.synchronize()
+    O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, True, w.scale, I.F16)
+    check(out.double().cpu().numpy(), lse.double().cpu().numpy(), O_ref, l_ref, I.F16, what="side stream")
+
+
+def test_errors_leave_outputs_untouched():
+    import torch
+    import paper_2403_16863_amd as A
+    q = torch.zeros(1, 1, 8, 64, dtype=torch.float16, device="cuda")
+    out = torch.full_like(q, 3.0)
+    lse = torch.full((1, 1, 8), 5.0, dtype=torch.float32, device="cuda")
+    with pytest.raises(A.AttnError) as e:
+        A.attn_fwd(q, q, q, q, lse, False, 1.0)            # out aliases q
+    assert e.value.code == -1
+    with pytest.raises(A.AttnError):
+        A.attn_fwd(q, q, q, out, lse, False, float("nan"))
+    with pytest.raises(A.AttnError):
+        A.attn_fwd_variant(q, q, q, out, lse, False, 1.0, A.attn_num_variants())
+    torch.cuda.synchronize()
+    assert (out == 3.0).all() and (lse == 5.0).all()
