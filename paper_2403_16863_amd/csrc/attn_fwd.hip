@@ -16,27 +16,24 @@ using attn::Params;
 typedef void (*KernelFn)(const Params);
 
 struct Variant {
-    int bn, nw, qb, occ;   // knob values
-    int coords[4];         // lattice coordinates (indices into the knob value lists)
+    int bn, nw, qb, occ, ldp;  // knob values
+    int coords[5];             // lattice coordinates (indices into the knob value lists)
     // kernels indexed [d == 128][dtype][causal]; null = not built for that combination
     KernelFn fn[2][2][2];
 };
 
 // Knob value lists (lattice axes).
-const int kBN[] = {32, 64, 128};
-const int kNW[] = {4, 8};
-const int kQB[] = {1, 2};
-const int kOCC[] = {1, 2};
-const char* const kKnobNames[] = {"bn", "nw", "qb", "occ"};
-const int kKnobSizes[] = {3, 2, 2, 2};
-constexpr int kNumKnobs = 4;
+const char* const kKnobNames[] = {"bn", "nw", "qb", "occ", "ldp"};
+const int kKnobSizes[] = {3, 2, 2, 2, 2};  // bn {32,64,128}  nw {4,8}  qb {1,2}  occ {1,2}  ldp {0,1}
+constexpr int kNumKnobs = 5;
 
-#define ATTN_KERNELS_FOR(BN, NW, QB, OCC, D)                                                     \
+#define ATTN_KN(BN, NW, QB, OCC, LDP) attn::Knobs<BN, NW, QB, OCC, LDP>
+#define ATTN_KERNELS_FOR(BN, NW, QB, OCC, LDP, D)                                                \
     {                                                                                            \
-        {(KernelFn)attn::attn_fwd_kernel<attn::F16, D, false, attn::Knobs<BN, NW, QB, OCC>>,       \
-         (KernelFn)attn::attn_fwd_kernel<attn::F16, D, true, attn::Knobs<BN, NW, QB, OCC>>},       \
-        {(KernelFn)attn::attn_fwd_kernel<attn::BF16, D, false, attn::Knobs<BN, NW, QB, OCC>>,      \
-         (KernelFn)attn::attn_fwd_kernel<attn::BF16, D, true, attn::Knobs<BN, NW, QB, OCC>>}       \
+        {(KernelFn)attn::attn_fwd_kernel<attn::F16, D, false, ATTN_KN(BN, NW, QB, OCC, LDP)>,      \
+         (KernelFn)attn::attn_fwd_kernel<attn::F16, D, true, ATTN_KN(BN, NW, QB, OCC, LDP)>},      \
+        {(KernelFn)attn::attn_fwd_kernel<attn::BF16, D, false, ATTN_KN(BN, NW, QB, OCC, LDP)>,     \
+         (KernelFn)attn::attn_fwd_kernel<attn::BF16, D, true, ATTN_KN(BN, NW, QB, OCC, LDP)>}      \
     }
 #define ATTN_NO_KERNELS {{nullptr, nullptr}, {nullptr, nullptr}}
 
@@ -46,22 +43,22 @@ constexpr int kNumKnobs = 4;
 #define IDX_QB(x) ((x) == 1 ? 0 : 1)
 #define IDX_OCC(x) ((x) == 1 ? 0 : 1)
 
-#define VARIANT_BOTH(BN, NW, QB, OCC)                                                            \
-    {BN, NW, QB, OCC, {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), IDX_OCC(OCC)},                          \
-     {ATTN_KERNELS_FOR(BN, NW, QB, OCC, 64), ATTN_KERNELS_FOR(BN, NW, QB, OCC, 128)}}
-#define VARIANT_D64(BN, NW, QB, OCC)                                                             \
-    {BN, NW, QB, OCC, {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), IDX_OCC(OCC)},                          \
-     {ATTN_KERNELS_FOR(BN, NW, QB, OCC, 64), ATTN_NO_KERNELS}}
+#define VARIANT_BOTH(BN, NW, QB, OCC, LDP)                                                       \
+    {BN, NW, QB, OCC, LDP, {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), IDX_OCC(OCC), LDP},                \
+     {ATTN_KERNELS_FOR(BN, NW, QB, OCC, LDP, 64), ATTN_KERNELS_FOR(BN, NW, QB, OCC, LDP, 128)}}
+#define VARIANT_D64(BN, NW, QB, OCC, LDP)                                                        \
+    {BN, NW, QB, OCC, LDP, {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), IDX_OCC(OCC), LDP},                \
+     {ATTN_KERNELS_FOR(BN, NW, QB, OCC, LDP, 64), ATTN_NO_KERNELS}}
 
 const Variant kVariants[] = {
-    VARIANT_BOTH(64, 4, 1, 2),   // 0: the hand-written default
-    VARIANT_BOTH(64, 4, 1, 1),
-    VARIANT_BOTH(32, 4, 1, 2),
-    VARIANT_BOTH(64, 4, 2, 1),
-    VARIANT_BOTH(32, 4, 2, 1),
-    VARIANT_BOTH(64, 8, 1, 1),
-    VARIANT_D64(128, 4, 1, 2),
-    VARIANT_D64(128, 4, 2, 1),
+    VARIANT_BOTH(64, 4, 1, 2, 0),   // 0: the hand-written default
+    VARIANT_BOTH(64, 4, 1, 2, 1),
+    VARIANT_BOTH(32, 4, 1, 2, 1),
+    VARIANT_BOTH(64, 4, 2, 1, 1),
+    VARIANT_BOTH(32, 4, 2, 1, 1),
+    VARIANT_BOTH(64, 8, 1, 1, 1),
+    VARIANT_D64(128, 4, 1, 2, 1),
+    VARIANT_D64(128, 4, 2, 1, 1),
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -123,6 +120,7 @@ int launch(const void* q, const void* k, const void* v, void* out, float* lse, i
     p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
     p.scale = scale > 0.f ? scale : (scale < 0.f ? -scale : 1.0f);
     p.scale_l2 = p.scale * 1.44269504088896340736f;
+    p.tau_raw = 8.0f / p.scale_l2;  // the reference maximum may lag the true one by 2^8
     // The launch's own return code is used (not hipGetLastError, which can report a
     // stale, unrelated status left behind by another library's earlier call).
     void* args[] = {&p};
@@ -147,8 +145,8 @@ int attn_variant_supported(int variant_id, int d, int dtype, int causal) {
 int attn_variant_desc(int variant_id, char* buf, int buflen) {
     if (variant_id < 0 || variant_id >= kNumVariants || !buf || buflen < 1) return ATTN_EINVAL;
     const Variant& v = kVariants[variant_id];
-    return snprintf(buf, (size_t)buflen, "bm=%d bn=%d nw=%d qb=%d occ=%d", 32 * v.qb * v.nw, v.bn,
-                    v.nw, v.qb, v.occ);
+    return snprintf(buf, (size_t)buflen, "bm=%d bn=%d nw=%d qb=%d occ=%d ldp=%d", 32 * v.qb * v.nw,
+                    v.bn, v.nw, v.qb, v.occ, v.ldp);
 }
 
 int attn_num_knobs(void) { return kNumKnobs; }

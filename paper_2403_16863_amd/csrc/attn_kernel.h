@@ -20,9 +20,14 @@
 //   A (32 x 16): lane l holds row l%32, k = 8*(l/32) .. +7
 //   B (16 x 32): lane l holds col l%32, k = 8*(l/32) .. +7
 //   C (32 x 32): lane l holds col l%32, register v holds row 8*(v/4) + 4*(l/32) + v%4
+// ds_read_b64_tr_b16 (checked on hardware): within each group of 16 lanes the 16 x 4
+// elements addressed by the lanes are taken as a row-major 4 x 16 block and lane i
+// receives column i, i.e. four consecutive rows of one column.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 namespace attn {
 
@@ -35,6 +40,9 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(1))) void* global_void_ptr;
+typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
 
 struct Params {
     const uint16_t* q;
@@ -43,12 +51,13 @@ struct Params {
     uint16_t* out;
     float* lse;
     int H, N;
-    int nqt;         // query tiles per head
-    int total_wg;    // nqt * B * H
-    float scale;     // multiplies q'.k, always > 0 (see qmode)
-    float scale_l2;  // scale * log2(e)
-    int qmode;       // 0: q' = q;  1: q' = -q (caller's scale was negative);
-                     // 2: q' = 0 (caller's scale was zero, kernel runs with scale 1)
+    int nqt;          // query tiles per head
+    int total_wg;     // nqt * B * H
+    float scale;      // multiplies q'.k, always > 0 (see qmode)
+    float scale_l2;   // scale * log2(e)
+    float tau_raw;    // lazy-rescale threshold in raw dot-product units (8 / scale_l2)
+    int qmode;        // 0: q' = q;  1: q' = -q (caller's scale was negative);
+                      // 2: q' = 0 (caller's scale was zero, kernel runs with scale 1)
 };
 
 struct F16 {
@@ -94,47 +103,43 @@ __device__ __forceinline__ float xhalf_max(float x) {
 }
 
 // ---- LDS layouts ------------------------------------------------------------
-// A K/V tile is BN rows of D 16-bit elements, addressed in 16-byte chunks.
-// K is read row-wise (ds_read_b128, lane = key row): chunks are XOR-swizzled with
+// A K/V tile is BN rows of D 16-bit elements, addressed in 16-byte chunks.  Both
+// swizzles below are involutions that keep a chunk inside its 256-byte line (K) or
+// its row (V), so the same function maps logical -> physical and physical -> logical.
+//
+// K is read row-wise (ds_read_b128, lane = key row): the chunk index is XOR-ed with
 // the 256-byte line index so 16 consecutive rows land on 16 distinct bank groups.
-template <int D>
-__device__ __forceinline__ int k_chunk_phys(int row, int cc) {
-    constexpr int CPR = D / 8;
-    const int L = row * CPR + cc;
-    return (L & ~15) | ((L ^ (L >> 4)) & 15);
-}
+__device__ __forceinline__ int k_swz(int chunk) { return (chunk & ~15) | ((chunk ^ (chunk >> 4)) & 15); }
 // V is read with the transposing load: a 16-lane group touches 4 consecutive key
 // rows x 32 bytes.  32-byte slots are XOR-ed with a code of (row & 3) chosen so the
 // four rows of one read and both lane groups of a half-wave hit disjoint banks.
 template <int D>
-__device__ __forceinline__ int v_byte_phys(int row, int dcol) {
-    constexpr int RB = D * 2;
+__device__ __forceinline__ int v_swz_slot(int row, int slot) {
     const int r = row & 3;
-    const int g = ((r << 1) & 6) | (r >> 1);  // 0,2,5,7
-    int slot = dcol >> 4;                     // 32-byte slot within the row
-    if (D == 128) slot ^= g;
-    else slot ^= (g & 3);                     // 4 slots per 128-byte row
-    return row * RB + slot * 32 + (dcol & 15) * 2;
+    const int code = ((r << 1) & 6) | (r >> 1);  // 0,2,5,7
+    return slot ^ (D == 128 ? code : (code & 3));
 }
 
 // Schedule / shape knobs of one variant (the lattice the search walks).
-template <int BN_, int NW_, int QB_, int OCC_>
+template <int BN_, int NW_, int QB_, int OCC_, int LDP_>
 struct Knobs {
     static constexpr int BN = BN_;    // keys per K/V tile
     static constexpr int NW = NW_;    // waves per workgroup
     static constexpr int QB = QB_;    // 32-row query blocks per wave
     static constexpr int OCC = OCC_;  // workgroups per CU the register budget aims for
+    static constexpr int LDP = LDP_;  // K/V load path: 0 = through VGPRs, 1 = global -> LDS directly
 };
 
 template <class T, int D, bool CAUSAL, class KN>
 __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Params p) {
-    constexpr int BN = KN::BN, NW = KN::NW, QB = KN::QB;
+    constexpr int BN = KN::BN, NW = KN::NW, QB = KN::QB, LDP = KN::LDP;
     constexpr int NT = NW * 64;
     constexpr int BM = 32 * QB * NW;
     constexpr int KS = D / 16;       // k-steps of the first contraction
     constexpr int DT = D / 32;       // 32-wide d tiles of O^T
     constexpr int KT = BN / 32;      // 32-key sub-tiles of one K/V tile
     constexpr int CPR = D / 8;       // 16-byte chunks per row
+    constexpr int RB = D * 2;        // bytes per row
     constexpr int TILE_CHUNKS = BN * CPR;
     constexpr int LD_PER_THREAD = TILE_CHUNKS / NT;
     static_assert(TILE_CHUNKS % NT == 0, "tile must divide over the workgroup");
@@ -145,7 +150,7 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5;
     const int c = lane & 31;
 
@@ -166,8 +171,8 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
 
     const size_t head_off = (size_t)bh * N * D;
     const uint16_t* __restrict__ Qh = p.q + head_off;
-    const uint16_t* __restrict__ Kh = p.k + head_off;
-    const uint16_t* __restrict__ Vh = p.v + head_off;
+    const char* __restrict__ Kh = reinterpret_cast<const char*>(p.k + head_off);
+    const char* __restrict__ Vh = reinterpret_cast<const char*>(p.v + head_off);
 
     // ---- Q as B operand, resident in registers
     u32x4 qreg[QB][KS];
@@ -185,10 +190,10 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
     }
 
     f32x16 o[QB][DT];
-    float m_run[QB], l_run[QB];
+    float m_use[QB], l_run[QB];  // reference maximum in use (raw units), partial row sum
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        m_run[qb] = -INFINITY;
+        m_use[qb] = -INFINITY;
         l_run[qb] = 0.f;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
@@ -200,159 +205,211 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
     const int kend = CAUSAL ? min(N, q0 + BM) : N;  // keys [0, kend)
     const int nkt = (kend + BN - 1) / BN;
 
-    // ---- global -> register staging of one K/V tile
-    u32x4 kst[LD_PER_THREAD], vst[LD_PER_THREAD];
-    auto load_tile = [&](int kt0) {
+    // ---- per-lane LDS read offsets (bytes inside one K or V tile), loop invariant.
+    // K: lane reads row (kt*32 + c), logical chunk (2*ks + g); moving kt by one adds
+    // 32 rows, which leaves the swizzle term unchanged, so kt is an immediate offset.
+    int koff[KS];
 #pragma unroll
-        for (int i = 0; i < LD_PER_THREAD; ++i) {
-            const int L = i * NT + tid;
-            const int row = L / CPR, cc = L % CPR;
-            u32x4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
-            if (kt0 + row < N) {
-                const size_t off = (size_t)(kt0 + row) * D + cc * 8;
-                kv = *reinterpret_cast<const u32x4*>(Kh + off);
-                vv = *reinterpret_cast<const u32x4*>(Vh + off);
+    for (int ks = 0; ks < KS; ++ks) koff[ks] = k_swz(c * CPR + 2 * ks + g) * 16;
+    // V: lane (16-lane group gq = lane/16, i = lane%16) addresses row 4*g + i/4 (+ 16*t + 8*hi
+    // + 32*kt, all multiples of 4, again immediates) and d column dt*32 + (gq&1)*16 + 4*(i%4).
+    int voff[DT];
+    {
+        const int i16 = lane & 15;
+        const int row = 4 * g + (i16 >> 2);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            const int dcol = dt * 32 + ((lane >> 4) & 1) * 16 + 4 * (i16 & 3);
+            voff[dt] = row * RB + v_swz_slot<D>(row, dcol >> 4) * 32 + (dcol & 15) * 2;
+        }
+    }
+
+    // ---- K/V tile movement.  Thread t moves chunks  i*NT + t  (i < LD_PER_THREAD) of the
+    // physical LDS tile; goff* are the byte offsets of the matching logical chunks in
+    // the row-major global tile.
+    int goffK[LD_PER_THREAD], goffV[LD_PER_THREAD], growK[LD_PER_THREAD], growV[LD_PER_THREAD];
+#pragma unroll
+    for (int i = 0; i < LD_PER_THREAD; ++i) {
+        const int P = i * NT + tid;
+        const int Lk = k_swz(P);
+        growK[i] = Lk / CPR;
+        goffK[i] = growK[i] * RB + (Lk % CPR) * 16;
+        const int rowv = P / CPR, pc = P % CPR;
+        growV[i] = rowv;
+        goffV[i] = rowv * RB + ((v_swz_slot<D>(rowv, pc >> 1) << 1) | (pc & 1)) * 16;
+    }
+    u32x4 kst[LDP == 0 ? LD_PER_THREAD : 1], vst[LDP == 0 ? LD_PER_THREAD : 1];
+
+    // global byte offset of logical chunk i for the tile starting at key kt0; rows past
+    // the end of the sequence are redirected to the last row (their scores are masked,
+    // so only finiteness of what is loaded matters)
+    auto src_off = [&](int kt0, int grow, int goff) -> size_t {
+        if (kt0 + BN <= N) return (size_t)kt0 * RB + goff;
+        const int r = min(kt0 + grow, N - 1);
+        return (size_t)r * RB + (goff - grow * RB);
+    };
+    auto issue_loads = [&](int kt0, int buf) {
+        if constexpr (LDP == 1) {
+            char* kb = smem_b + buf * 2 * TILE_BYTES;
+            char* vb = kb + TILE_BYTES;
+#pragma unroll
+            for (int i = 0; i < LD_PER_THREAD; ++i) {
+                const int wbase = (i * NT + wave * 64) * 16;  // wave-uniform LDS destination
+                __builtin_amdgcn_global_load_lds((global_void_ptr)(Kh + src_off(kt0, growK[i], goffK[i])),
+                                                 (lds_void_ptr)(kb + wbase), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((global_void_ptr)(Vh + src_off(kt0, growV[i], goffV[i])),
+                                                 (lds_void_ptr)(vb + wbase), 16, 0, 0);
             }
-            kst[i] = kv;
-            vst[i] = vv;
-        }
-    };
-    auto store_tile = [&](int buf) {
-        char* kb = smem_b + buf * 2 * TILE_BYTES;
-        char* vb = kb + TILE_BYTES;
+        } else {
 #pragma unroll
-        for (int i = 0; i < LD_PER_THREAD; ++i) {
-            const int L = i * NT + tid;
-            const int row = L / CPR, cc = L % CPR;
-            *reinterpret_cast<u32x4*>(kb + k_chunk_phys<D>(row, cc) * 16) = kst[i];
-            *reinterpret_cast<u32x4*>(vb + v_byte_phys<D>(row, cc * 8)) = vst[i];
+            for (int i = 0; i < LD_PER_THREAD; ++i) {
+                kst[i] = *reinterpret_cast<const u32x4*>(Kh + src_off(kt0, growK[i], goffK[i]));
+                vst[i] = *reinterpret_cast<const u32x4*>(Vh + src_off(kt0, growV[i], goffV[i]));
+            }
+        }
+    };
+    auto land_loads = [&](int buf) {  // make the tile issued last visible in LDS to this thread
+        if constexpr (LDP == 1) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        } else {
+            char* kb = smem_b + buf * 2 * TILE_BYTES;
+            char* vb = kb + TILE_BYTES;
+#pragma unroll
+            for (int i = 0; i < LD_PER_THREAD; ++i) {
+                *reinterpret_cast<u32x4*>(kb + (i * NT + tid) * 16) = kst[i];
+                *reinterpret_cast<u32x4*>(vb + (i * NT + tid) * 16) = vst[i];
+            }
         }
     };
 
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-
-    for (int j = 0; j < nkt; ++j) {
-        const int k0 = j * BN;
-        const bool more = (j + 1 < nkt);
-        if (more) load_tile(k0 + BN);
-
-        const char* kb = smem_b + (j & 1) * 2 * TILE_BYTES;
+    // ---- one K/V tile: S^T, mask, online softmax, O^T update.  BUF is a compile-time
+    // buffer index so every LDS offset folds into the instructions' immediates.
+    auto compute_tile = [&](auto buf_c, int k0) {
+        constexpr int BUF = decltype(buf_c)::value;
+        const char* kb = smem_b + BUF * 2 * TILE_BYTES;
         const char* vb = kb + TILE_BYTES;
 
-        // causal: a wave whose queries all precede this tile has nothing to do
-        const bool active = !CAUSAL || (k0 <= qw0 + 32 * QB - 1);
-        if (active) {
-            // ---- S^T = K . Q^T
-            f32x16 s[QB][KT];
+        // S^T = K . Q^T ; the KT accumulators are independent, alternate between them
+        f32x16 s[QB][KT];
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
+        for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-                for (int kt = 0; kt < KT; ++kt)
+            for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) s[qb][kt][v] = 0.f;
+                for (int v = 0; v < 16; ++v) s[qb][kt][v] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
             for (int kt = 0; kt < KT; ++kt) {
+                const u32x4 a = *reinterpret_cast<const u32x4*>(kb + kt * 32 * RB + koff[ks]);
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const u32x4 a = *reinterpret_cast<const u32x4*>(
-                        kb + k_chunk_phys<D>(kt * 32 + c, ks * 2 + g) * 16);
-#pragma unroll
-                    for (int qb = 0; qb < QB; ++qb) s[qb][kt] = T::mfma(a, qreg[qb][ks], s[qb][kt]);
-                }
+                for (int qb = 0; qb < QB; ++qb) s[qb][kt] = T::mfma(a, qreg[qb][ks], s[qb][kt]);
             }
+        }
 
-            // ---- mask: keys past the end of the sequence, and keys after the query
-            const bool need_mask = (k0 + BN > N) || (CAUSAL && (k0 + BN - 1 > qw0));
-            if (need_mask) {
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    const int qi = qw0 + qb * 32 + c;
-                    const int lim = CAUSAL ? min(qi, N - 1) : N - 1;  // last visible key
-#pragma unroll
-                    for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const int key = k0 + kt * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                            if (key > lim) s[qb][kt][v] = -INFINITY;
-                        }
-                }
-            }
-
-            // ---- online softmax (per query = per lane column), P^T packed as B operand
-            u32x4 pk[QB][KT][2];
+        // mask: keys past the end of the sequence, and keys after the query
+        const bool need_mask = (k0 + BN > N) || (CAUSAL && (k0 + BN - 1 > qw0));
+        if (need_mask) {
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
-                float mx = s[qb][0][0];
+                const int qi = qw0 + qb * 32 + c;
+                const int lim = CAUSAL ? min(qi, N - 1) : N - 1;  // last visible key
 #pragma unroll
                 for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[qb][kt][v]);
-                mx = xhalf_max(mx);
-                const float m_new = fmaxf(m_run[qb], mx);
-                // m_new is finite: key 0 is visible to every query and lives in tile 0
-                // first tile: m_run = -inf and alpha must be 0 even when scale is 0
-                const float alpha = (m_run[qb] == -INFINITY)
-                                        ? 0.f
-                                        : __builtin_amdgcn_exp2f((m_run[qb] - m_new) * p.scale_l2);
-                const float mb = m_new * p.scale_l2;
-                m_run[qb] = m_new;
-                float rs = 0.f;
-#pragma unroll
-                for (int kt = 0; kt < KT; ++kt) {
-                    float e[16];
-#pragma unroll
                     for (int v = 0; v < 16; ++v) {
-                        e[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][kt][v], p.scale_l2, -mb));
-                        rs += e[v];
+                        const int key = k0 + kt * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                        if (key > lim) s[qb][kt][v] = -INFINITY;
                     }
+            }
+        }
+
+        // online softmax (per query = per lane column), P^T packed as B operand.
+        // The reference maximum m_use is only raised when the tile maximum exceeds it by
+        // more than tau (2^8 in probability units): P may then be as large as 2^8, which
+        // fp32 sums and 16-bit P hold without loss, and the O accumulators are rescaled
+        // only on those rare tiles.  The final normalisation divides by the true sum, so
+        // the result is the same function.
+        u32x4 pk[QB][KT][2];
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        u32x4 w;
-                        w[0] = T::pack2(e[8 * t + 0], e[8 * t + 1]);
-                        w[1] = T::pack2(e[8 * t + 2], e[8 * t + 3]);
-                        w[2] = T::pack2(e[8 * t + 4], e[8 * t + 5]);
-                        w[3] = T::pack2(e[8 * t + 6], e[8 * t + 7]);
-                        pk[qb][kt][t] = w;
-                    }
-                }
-                l_run[qb] = l_run[qb] * alpha + rs;
+        for (int qb = 0; qb < QB; ++qb) {
+            float mx = s[qb][0][0];
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[qb][kt][v]);
+            mx = xhalf_max(mx);
+            if (__builtin_amdgcn_ballot_w64(mx > m_use[qb] + p.tau_raw) != 0) {  // wave-uniform
+                const float m_new = fmaxf(m_use[qb], mx);
+                // m_new is finite (key 0 is visible to every query and lives in tile 0);
+                // on the first tile m_use is -inf and alpha = exp2(-inf) = 0
+                const float alpha = __builtin_amdgcn_exp2f((m_use[qb] - m_new) * p.scale_l2);
+                m_use[qb] = m_new;
+                l_run[qb] *= alpha;
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) o[qb][dt][v] *= alpha;
             }
-
-            // ---- O^T += V^T . P^T
-            // k-slot s of step (kt, t) for lane group g is key kt*32 + 16*t + 8*(s/4) + 4*g + s%4
+            const float mb = m_use[qb] * p.scale_l2;
+            float rs0 = 0.f, rs1 = 0.f;  // row sum of the unrounded probabilities, fp32
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
+            for (int kt = 0; kt < KT; ++kt) {
 #pragma unroll
-                for (int kt = 0; kt < KT; ++kt) {
+                for (int t = 0; t < 2; ++t) {
+                    u32x4 w;
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        const int i16 = lane & 15;
-                        const int dcol = dt * 32 + ((lane >> 4) & 1) * 16 + 4 * (i16 & 3);
-                        const int krow = kt * 32 + 16 * t + 4 * g + (i16 >> 2);
-                        typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
-                        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (lds_s16x4_ptr)(vb + v_byte_phys<D>(krow, dcol)));
-                        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (lds_s16x4_ptr)(vb + v_byte_phys<D>(krow + 8, dcol)));
-                        u32x4 a;
-                        const u32x2 lo2 = __builtin_bit_cast(u32x2, lo);
-                        const u32x2 hi2 = __builtin_bit_cast(u32x2, hi);
-                        a[0] = lo2[0]; a[1] = lo2[1]; a[2] = hi2[0]; a[3] = hi2[1];
-#pragma unroll
-                        for (int qb = 0; qb < QB; ++qb) o[qb][dt] = T::mfma(a, pk[qb][kt][t], o[qb][dt]);
+                    for (int h = 0; h < 4; ++h) {
+                        const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][kt][8 * t + 2 * h], p.scale_l2, -mb));
+                        const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][kt][8 * t + 2 * h + 1], p.scale_l2, -mb));
+                        w[h] = T::pack2(e0, e1);
+                        rs0 += e0;
+                        rs1 += e1;
                     }
+                    pk[qb][kt][t] = w;
+                }
+            }
+            l_run[qb] += rs0 + rs1;
+        }
+
+        // O^T += V^T . P^T
+        // k-slot s of step (kt, t) for lane group g is key kt*32 + 16*t + 8*(s/4) + 4*g + s%4
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const char* base = vb + (kt * 32 + 16 * t) * RB + voff[dt];
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(base));
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(base + 8 * RB));
+                    const u32x2 lo2 = __builtin_bit_cast(u32x2, lo);
+                    const u32x2 hi2 = __builtin_bit_cast(u32x2, hi);
+                    const u32x4 a = {lo2[0], lo2[1], hi2[0], hi2[1]};
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb) o[qb][dt] = T::mfma(a, pk[qb][kt][t], o[qb][dt]);
                 }
             }
         }
+    };
 
-        if (more) store_tile((j + 1) & 1);
+    auto step = [&](auto buf_c, int j) {
+        constexpr int BUF = decltype(buf_c)::value;
+        const int k0 = j * BN;
+        const bool more = (j + 1 < nkt);
+        if (more) issue_loads(k0 + BN, BUF ^ 1);
+        // causal: a wave whose queries all precede this tile has nothing to compute
+        if (!CAUSAL || (k0 <= qw0 + 32 * QB - 1)) compute_tile(buf_c, k0);
+        if (more) land_loads(BUF ^ 1);
         __syncthreads();
+    };
+
+    issue_loads(0, 0);
+    land_loads(0);
+    __syncthreads();
+    for (int j = 0; j < nkt; j += 2) {
+        step(std::integral_constant<int, 0>{}, j);
+        if (j + 1 < nkt) step(std::integral_constant<int, 1>{}, j + 1);
     }
 
     // ---- epilogue: normalise, round once, store O and lse
@@ -372,7 +429,7 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
                     w[1] = T::pack2(o[qb][dt][4 * v4 + 2] * inv, o[qb][dt][4 * v4 + 3] * inv);
                     *reinterpret_cast<u32x2*>(orow + dt * 32 + 8 * v4 + 4 * g) = w;
                 }
-            if (g == 0) p.lse[(size_t)bh * N + qi] = m_run[qb] * p.scale + __logf(l_tot);
+            if (g == 0) p.lse[(size_t)bh * N + qi] = m_use[qb] * p.scale + __logf(l_tot);
         }
     }
 }
