@@ -16,24 +16,25 @@ using attn::Params;
 typedef void (*KernelFn)(const Params);
 
 struct Variant {
-    int bn, nw, qb, occ, ldp;  // knob values
-    int coords[5];             // lattice coordinates (indices into the knob value lists)
+    int bn, nw, qb, occ, ldp, pipe, pf, prio;  // knob values
+    int coords[8];                             // lattice coordinates (indices into the knob value lists)
     // kernels indexed [d == 128][dtype][causal]; null = not built for that combination
     KernelFn fn[2][2][2];
 };
 
-// Knob value lists (lattice axes).
-const char* const kKnobNames[] = {"bn", "nw", "qb", "occ", "ldp"};
-const int kKnobSizes[] = {3, 2, 2, 2, 2};  // bn {32,64,128}  nw {4,8}  qb {1,2}  occ {1,2}  ldp {0,1}
-constexpr int kNumKnobs = 5;
+// Knob value lists (lattice axes): bn {32,64,128}  nw {4,8}  qb {1,2}  occ {1,2}  ldp {0,1}
+// pipe {0,1}  pf {2,4,6,8}  prio {0,1}
+const char* const kKnobNames[] = {"bn", "nw", "qb", "occ", "ldp", "pipe", "pf", "prio"};
+const int kKnobSizes[] = {3, 2, 2, 2, 2, 2, 4, 2};
+constexpr int kNumKnobs = 8;
 
-#define ATTN_KN(BN, NW, QB, OCC, LDP) attn::Knobs<BN, NW, QB, OCC, LDP>
-#define ATTN_KERNELS_FOR(BN, NW, QB, OCC, LDP, D)                                                \
-    {                                                                                            \
-        {(KernelFn)attn::attn_fwd_kernel<attn::F16, D, false, ATTN_KN(BN, NW, QB, OCC, LDP)>,      \
-         (KernelFn)attn::attn_fwd_kernel<attn::F16, D, true, ATTN_KN(BN, NW, QB, OCC, LDP)>},      \
-        {(KernelFn)attn::attn_fwd_kernel<attn::BF16, D, false, ATTN_KN(BN, NW, QB, OCC, LDP)>,     \
-         (KernelFn)attn::attn_fwd_kernel<attn::BF16, D, true, ATTN_KN(BN, NW, QB, OCC, LDP)>}      \
+#define ATTN_KN(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO) attn::Knobs<BN, NW, QB, OCC, LDP, PIPE, PF, PRIO>
+#define ATTN_KERNELS_FOR(D, ...)                                                        \
+    {                                                                                   \
+        {(KernelFn)attn::attn_fwd_kernel<attn::F16, D, false, ATTN_KN(__VA_ARGS__)>,      \
+         (KernelFn)attn::attn_fwd_kernel<attn::F16, D, true, ATTN_KN(__VA_ARGS__)>},      \
+        {(KernelFn)attn::attn_fwd_kernel<attn::BF16, D, false, ATTN_KN(__VA_ARGS__)>,     \
+         (KernelFn)attn::attn_fwd_kernel<attn::BF16, D, true, ATTN_KN(__VA_ARGS__)>}      \
     }
 #define ATTN_NO_KERNELS {{nullptr, nullptr}, {nullptr, nullptr}}
 
@@ -42,23 +43,32 @@ constexpr int kNumKnobs = 5;
 #define IDX_NW(x) ((x) == 4 ? 0 : 1)
 #define IDX_QB(x) ((x) == 1 ? 0 : 1)
 #define IDX_OCC(x) ((x) == 1 ? 0 : 1)
+#define IDX_PF(x) ((x) / 2 - 1)
 
-#define VARIANT_BOTH(BN, NW, QB, OCC, LDP)                                                       \
-    {BN, NW, QB, OCC, LDP, {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), IDX_OCC(OCC), LDP},                \
-     {ATTN_KERNELS_FOR(BN, NW, QB, OCC, LDP, 64), ATTN_KERNELS_FOR(BN, NW, QB, OCC, LDP, 128)}}
-#define VARIANT_D64(BN, NW, QB, OCC, LDP)                                                        \
-    {BN, NW, QB, OCC, LDP, {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), IDX_OCC(OCC), LDP},                \
-     {ATTN_KERNELS_FOR(BN, NW, QB, OCC, LDP, 64), ATTN_NO_KERNELS}}
+#define VARIANT_BOTH(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)                                          \
+    {BN, NW, QB, OCC, LDP, PIPE, PF, PRIO,                                                          \
+     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), IDX_OCC(OCC), LDP, PIPE, IDX_PF(PF), PRIO},               \
+     {ATTN_KERNELS_FOR(64, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO),                                   \
+      ATTN_KERNELS_FOR(128, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)}}
+#define VARIANT_D64(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)                                           \
+    {BN, NW, QB, OCC, LDP, PIPE, PF, PRIO,                                                          \
+     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), IDX_OCC(OCC), LDP, PIPE, IDX_PF(PF), PRIO},               \
+     {ATTN_KERNELS_FOR(64, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO), ATTN_NO_KERNELS}}
 
 const Variant kVariants[] = {
-    VARIANT_BOTH(64, 4, 1, 2, 0),   // 0: the hand-written default
-    VARIANT_BOTH(64, 4, 1, 2, 1),
-    VARIANT_BOTH(32, 4, 1, 2, 1),
-    VARIANT_BOTH(64, 4, 2, 1, 1),
-    VARIANT_BOTH(32, 4, 2, 1, 1),
-    VARIANT_BOTH(64, 8, 1, 1, 1),
-    VARIANT_D64(128, 4, 1, 2, 1),
-    VARIANT_D64(128, 4, 2, 1, 1),
+    VARIANT_BOTH(64, 4, 1, 2, 1, 0, 4, 0),   // 0: the hand-written default
+    VARIANT_BOTH(64, 4, 1, 2, 1, 0, 2, 0),
+    VARIANT_BOTH(64, 4, 1, 2, 1, 0, 6, 0),
+    VARIANT_BOTH(64, 4, 1, 2, 1, 0, 4, 1),
+    VARIANT_BOTH(64, 4, 1, 2, 0, 0, 4, 0),
+    VARIANT_BOTH(32, 4, 1, 2, 1, 0, 4, 0),
+    VARIANT_BOTH(64, 8, 1, 1, 1, 0, 4, 0),
+    VARIANT_BOTH(64, 8, 1, 1, 1, 1, 4, 0),
+    VARIANT_BOTH(64, 8, 1, 1, 1, 1, 6, 0),
+    VARIANT_BOTH(64, 8, 1, 1, 1, 1, 6, 1),
+    VARIANT_BOTH(64, 8, 1, 1, 1, 1, 8, 1),
+    VARIANT_BOTH(64, 4, 2, 1, 1, 0, 4, 0),
+    VARIANT_D64(128, 4, 1, 2, 1, 0, 4, 0),
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -120,7 +130,6 @@ int launch(const void* q, const void* k, const void* v, void* out, float* lse, i
     p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
     p.scale = scale > 0.f ? scale : (scale < 0.f ? -scale : 1.0f);
     p.scale_l2 = p.scale * 1.44269504088896340736f;
-    p.tau_raw = 8.0f / p.scale_l2;  // the reference maximum may lag the true one by 2^8
     // The launch's own return code is used (not hipGetLastError, which can report a
     // stale, unrelated status left behind by another library's earlier call).
     void* args[] = {&p};
@@ -145,8 +154,8 @@ int attn_variant_supported(int variant_id, int d, int dtype, int causal) {
 int attn_variant_desc(int variant_id, char* buf, int buflen) {
     if (variant_id < 0 || variant_id >= kNumVariants || !buf || buflen < 1) return ATTN_EINVAL;
     const Variant& v = kVariants[variant_id];
-    return snprintf(buf, (size_t)buflen, "bm=%d bn=%d nw=%d qb=%d occ=%d ldp=%d", 32 * v.qb * v.nw,
-                    v.bn, v.nw, v.qb, v.occ, v.ldp);
+    return snprintf(buf, (size_t)buflen, "bm=%d bn=%d nw=%d qb=%d occ=%d ldp=%d pipe=%d pf=%d prio=%d",
+                    32 * v.qb * v.nw, v.bn, v.nw, v.qb, v.occ, v.ldp, v.pipe, v.pf, v.prio);
 }
 
 int attn_num_knobs(void) { return kNumKnobs; }

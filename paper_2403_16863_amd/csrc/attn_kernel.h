@@ -55,7 +55,6 @@ struct Params {
     int total_wg;     // nqt * B * H
     float scale;      // multiplies q'.k, always > 0 (see qmode)
     float scale_l2;   // scale * log2(e)
-    float tau_raw;    // lazy-rescale threshold in raw dot-product units (8 / scale_l2)
     int qmode;        // 0: q' = q;  1: q' = -q (caller's scale was negative);
                       // 2: q' = 0 (caller's scale was zero, kernel runs with scale 1)
 };
@@ -121,18 +120,22 @@ __device__ __forceinline__ int v_swz_slot(int row, int slot) {
 }
 
 // Schedule / shape knobs of one variant (the lattice the search walks).
-template <int BN_, int NW_, int QB_, int OCC_, int LDP_>
+template <int BN_, int NW_, int QB_, int OCC_, int LDP_, int PIPE_, int PF_, int PRIO_>
 struct Knobs {
-    static constexpr int BN = BN_;    // keys per K/V tile
-    static constexpr int NW = NW_;    // waves per workgroup
-    static constexpr int QB = QB_;    // 32-row query blocks per wave
-    static constexpr int OCC = OCC_;  // workgroups per CU the register budget aims for
-    static constexpr int LDP = LDP_;  // K/V load path: 0 = through VGPRs, 1 = global -> LDS directly
+    static constexpr int BN = BN_;      // keys per K/V tile
+    static constexpr int NW = NW_;      // waves per workgroup
+    static constexpr int QB = QB_;      // 32-row query blocks per wave
+    static constexpr int OCC = OCC_;    // workgroups per CU the register budget aims for
+    static constexpr int LDP = LDP_;    // K/V load path: 0 = through VGPRs, 1 = global -> LDS directly
+    static constexpr int PIPE = PIPE_;  // 0 = per tile S, softmax, PV, waves run free;
+                                        // 1 = two-cluster ping-pong between the two waves of a SIMD
+    static constexpr int PF = PF_;      // LDS fragment prefetch distance of the MFMA streams, in MFMA steps
+    static constexpr int PRIO = PRIO_;  // 1 = raise the wave priority (s_setprio) while it runs an MFMA stream
 };
 
 template <class T, int D, bool CAUSAL, class KN>
 __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Params p) {
-    constexpr int BN = KN::BN, NW = KN::NW, QB = KN::QB, LDP = KN::LDP;
+    constexpr int BN = KN::BN, NW = KN::NW, QB = KN::QB, LDP = KN::LDP, PIPE = KN::PIPE, PF = KN::PF, PRIO = KN::PRIO;
     constexpr int NT = NW * 64;
     constexpr int BM = 32 * QB * NW;
     constexpr int KS = D / 16;       // k-steps of the first contraction
@@ -144,6 +147,8 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
     constexpr int LD_PER_THREAD = TILE_CHUNKS / NT;
     static_assert(TILE_CHUNKS % NT == 0, "tile must divide over the workgroup");
     constexpr int TILE_BYTES = TILE_CHUNKS * 16;
+    constexpr int NVF = KT * 2 * DT;  // V fragments (MFMA steps of the second contraction) per tile
+    constexpr int NKF = KS * KT;      // K fragments (MFMA steps of the first contraction) per tile
 
     __shared__ __attribute__((aligned(256))) u32x4 smem[4 * TILE_CHUNKS];  // K0 V0 K1 V1
     char* const smem_b = reinterpret_cast<char*>(smem);
@@ -168,6 +173,7 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
     const int N = p.N;
     const int q0 = qt * BM;
     const int qw0 = q0 + wave * (32 * QB);  // first query row of this wave
+    const int qw_last = qw0 + 32 * QB - 1;  // causal: tile j is active for this wave iff j*BN <= qw_last
 
     const size_t head_off = (size_t)bh * N * D;
     const uint16_t* __restrict__ Qh = p.q + head_off;
@@ -204,6 +210,7 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
     // key tiles this workgroup visits
     const int kend = CAUSAL ? min(N, q0 + BM) : N;  // keys [0, kend)
     const int nkt = (kend + BN - 1) / BN;
+    auto tile_active = [&](int j) __attribute__((always_inline)) { return j < nkt && (!CAUSAL || j * BN <= qw_last); };
 
     // ---- per-lane LDS read offsets (bytes inside one K or V tile), loop invariant.
     // K: lane reads row (kt*32 + c), logical chunk (2*ks + g); moving kt by one adds
@@ -224,51 +231,60 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
         }
     }
 
+    // All helper lambdas below are force-inlined: they capture the register arrays (o, s,
+    // pk, qreg ...) by reference, and a call that is not inlined would push those arrays
+    // out of registers into scratch memory.
+
     // ---- K/V tile movement.  Thread t moves chunks  i*NT + t  (i < LD_PER_THREAD) of the
-    // physical LDS tile; goff* are the byte offsets of the matching logical chunks in
-    // the row-major global tile.
-    int goffK[LD_PER_THREAD], goffV[LD_PER_THREAD], growK[LD_PER_THREAD], growV[LD_PER_THREAD];
-#pragma unroll
-    for (int i = 0; i < LD_PER_THREAD; ++i) {
-        const int P = i * NT + tid;
-        const int Lk = k_swz(P);
-        growK[i] = Lk / CPR;
-        goffK[i] = growK[i] * RB + (Lk % CPR) * 16;
-        const int rowv = P / CPR, pc = P % CPR;
-        growV[i] = rowv;
-        goffV[i] = rowv * RB + ((v_swz_slot<D>(rowv, pc >> 1) << 1) | (pc & 1)) * 16;
+    // physical LDS tile.  NT is a multiple of 256, so step i advances by a whole number of
+    // swizzle periods and the matching logical chunk in the row-major global tile is
+    //     goff0 + i * ROWS_PER_STEP * RB      (goff0 per lane, the rest compile-time).
+    static_assert(NT % 256 == 0, "load mapping assumes whole swizzle periods per step");
+    constexpr int ROWS_PER_STEP = NT / CPR;
+    unsigned goffK0, goffV0;
+    {
+        const int Lk = k_swz(tid);
+        goffK0 = (unsigned)((Lk / CPR) * RB + (Lk % CPR) * 16);
+        const int rowv = tid / CPR, pc = tid % CPR;
+        goffV0 = (unsigned)(rowv * RB + ((v_swz_slot<D>(rowv, pc >> 1) << 1) | (pc & 1)) * 16);
     }
     u32x4 kst[LDP == 0 ? LD_PER_THREAD : 1], vst[LDP == 0 ? LD_PER_THREAD : 1];
 
-    // global byte offset of logical chunk i for the tile starting at key kt0; rows past
-    // the end of the sequence are redirected to the last row (their scores are masked,
-    // so only finiteness of what is loaded matters)
-    auto src_off = [&](int kt0, int grow, int goff) -> size_t {
-        if (kt0 + BN <= N) return (size_t)kt0 * RB + goff;
-        const int r = min(kt0 + grow, N - 1);
-        return (size_t)r * RB + (goff - grow * RB);
-    };
-    auto issue_loads = [&](int kt0, int buf) {
-        if constexpr (LDP == 1) {
-            char* kb = smem_b + buf * 2 * TILE_BYTES;
-            char* vb = kb + TILE_BYTES;
+    // One tile = LD_PER_THREAD steps; the source of step i is a wave-uniform base (tile
+    // start + i * ROWS_PER_STEP rows) plus the per-lane 32-bit offset.  The tile index is
+    // clamped to the last tile (a redundant reload into a buffer nobody reads any more is
+    // cheaper than a branch in every iteration).  Only the last, ragged tile takes the
+    // slow path, where rows past the end of the sequence are redirected to the last row
+    // (their scores are masked, so only finiteness of what is loaded matters).
+    auto issue_tile = [&](const char* head, unsigned goff0, int j, char* lds_tile, u32x4(&stage)[LDP == 0 ? LD_PER_THREAD : 1]) __attribute__((always_inline)) {
+        const int kt0 = min(j, nkt - 1) * BN;
+        if (kt0 + BN <= N) {
+            const char* tb = head + (size_t)kt0 * RB;
 #pragma unroll
             for (int i = 0; i < LD_PER_THREAD; ++i) {
-                const int wbase = (i * NT + wave * 64) * 16;  // wave-uniform LDS destination
-                __builtin_amdgcn_global_load_lds((global_void_ptr)(Kh + src_off(kt0, growK[i], goffK[i])),
-                                                 (lds_void_ptr)(kb + wbase), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds((global_void_ptr)(Vh + src_off(kt0, growV[i], goffV[i])),
-                                                 (lds_void_ptr)(vb + wbase), 16, 0, 0);
+                const char* src = tb + (size_t)(i * ROWS_PER_STEP * RB) + goff0;
+                if constexpr (LDP == 1)
+                    __builtin_amdgcn_global_load_lds((global_void_ptr)src, (lds_void_ptr)(lds_tile + (i * NT + wave * 64) * 16), 16, 0, 0);
+                else
+                    stage[i] = *reinterpret_cast<const u32x4*>(src);
             }
         } else {
+            const int row0 = (int)(goff0 / RB);
+            const unsigned col = goff0 % RB;
 #pragma unroll
             for (int i = 0; i < LD_PER_THREAD; ++i) {
-                kst[i] = *reinterpret_cast<const u32x4*>(Kh + src_off(kt0, growK[i], goffK[i]));
-                vst[i] = *reinterpret_cast<const u32x4*>(Vh + src_off(kt0, growV[i], goffV[i]));
+                const int r = min(kt0 + row0 + i * ROWS_PER_STEP, N - 1);
+                const char* src = head + (size_t)r * RB + col;
+                if constexpr (LDP == 1)
+                    __builtin_amdgcn_global_load_lds((global_void_ptr)src, (lds_void_ptr)(lds_tile + (i * NT + wave * 64) * 16), 16, 0, 0);
+                else
+                    stage[i] = *reinterpret_cast<const u32x4*>(src);
             }
         }
     };
-    auto land_loads = [&](int buf) {  // make the tile issued last visible in LDS to this thread
+    auto issue_k = [&](int j, int buf) __attribute__((always_inline)) { issue_tile(Kh, goffK0, j, smem_b + buf * 2 * TILE_BYTES, kst); };
+    auto issue_v = [&](int j, int buf) __attribute__((always_inline)) { issue_tile(Vh, goffV0, j, smem_b + buf * 2 * TILE_BYTES + TILE_BYTES, vst); };
+    auto land_loads = [&](int buf) __attribute__((always_inline)) {  // make the tiles issued last visible in LDS to this thread
         if constexpr (LDP == 1) {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         } else {
@@ -282,32 +298,74 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
         }
     };
 
-    // ---- one K/V tile: S^T, mask, online softmax, O^T update.  BUF is a compile-time
-    // buffer index so every LDS offset folds into the instructions' immediates.
-    auto compute_tile = [&](auto buf_c, int k0) {
-        constexpr int BUF = decltype(buf_c)::value;
-        const char* kb = smem_b + BUF * 2 * TILE_BYTES;
-        const char* vb = kb + TILE_BYTES;
-
-        // S^T = K . Q^T ; the KT accumulators are independent, alternate between them
-        f32x16 s[QB][KT];
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-            for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) s[qb][kt][v] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-            for (int kt = 0; kt < KT; ++kt) {
-                const u32x4 a = *reinterpret_cast<const u32x4*>(kb + kt * 32 * RB + koff[ks]);
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) s[qb][kt] = T::mfma(a, qreg[qb][ks], s[qb][kt]);
+    // ---- MFMA work as a software-pipelined stream: NVF steps of O^T += V^T P^T (each needs
+    // one V fragment = two transposing reads; k-slot s of step (kt, t) for lane group g is
+    // key kt*32 + 16*t + 8*(s/4) + 4*g + s%4) and/or NKF steps of S^T = K Q^T (one 16-byte K
+    // fragment each, alternating between the KT independent accumulators).  Fragments are
+    // read PF steps ahead into a ring of registers, in source order pinned by scheduling
+    // fences, so an MFMA never waits for an LDS read issued just before it.  Buffer indices
+    // are compile-time constants so every LDS offset folds into the instruction.
+    auto mfma_stream = [&](auto has_pv_c, auto has_qk_c, auto vbuf_c, auto kbuf_c,
+                           const u32x4(&pk)[QB][KT][2], f32x16(&s)[QB][KT]) __attribute__((always_inline)) {
+        constexpr bool HAS_PV = decltype(has_pv_c)::value, HAS_QK = decltype(has_qk_c)::value;
+        constexpr int VB = decltype(vbuf_c)::value, KB = decltype(kbuf_c)::value;
+        constexpr int N0 = HAS_PV ? NVF : 0, NS = N0 + (HAS_QK ? NKF : 0);
+        const char* vb = smem_b + VB * 2 * TILE_BYTES + TILE_BYTES;
+        const char* kb = smem_b + KB * 2 * TILE_BYTES;
+        auto read_frag = [&](int i) __attribute__((always_inline)) -> u32x4 {
+            if (i < N0) {  // V fragment i = (kt*2 + t)*DT + dt
+                const int dt = i % DT, t = (i / DT) & 1, kt = i / (2 * DT);
+                const char* base = vb + (kt * 32 + 16 * t) * RB + voff[dt];
+                const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(base)));
+                const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(base + 8 * RB)));
+                return u32x4{lo[0], lo[1], hi[0], hi[1]};
+            } else {       // K fragment f = ks*KT + kt
+                const int f = i - N0;
+                return *reinterpret_cast<const u32x4*>(kb + (f % KT) * 32 * RB + koff[f / KT]);
             }
+        };
+        if constexpr (HAS_QK) {
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) s[qb][kt][v] = 0.f;
         }
+        if constexpr (PRIO == 1) __builtin_amdgcn_s_setprio(2);
+        constexpr int NPRE = PF < NS ? PF : NS;
+        u32x4 ring[PF];
+#pragma unroll
+        for (int i = 0; i < NPRE; ++i) ring[i] = read_frag(i);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            if (i < N0) {
+                const int dt = i % DT, t = (i / DT) & 1, kt = i / (2 * DT);
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) o[qb][dt] = T::mfma(ring[i % PF], pk[qb][kt][t], o[qb][dt]);
+            } else {
+                const int f = i - N0, ks = f / KT, kt = f % KT;
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) s[qb][kt] = T::mfma(ring[i % PF], qreg[qb][ks], s[qb][kt]);
+            }
+            if (i + PF < NS) ring[i % PF] = read_frag(i + PF);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (PRIO == 1) __builtin_amdgcn_s_setprio(0);
+    };
 
-        // mask: keys past the end of the sequence, and keys after the query
+    // ---- softmax of one tile (per query = per lane column): S -> P^T packed as B operand.
+    //
+    // P = exp2(scale_l2 * (S - m_use)) with a reference maximum m_use that is NOT updated on
+    // every tile: the probabilities are first formed against the current reference, and
+    // only if a lane's partial row sum leaves [0, 2^8] (a score grew past the reference by a
+    // lot, or this is the first tile, where m_use = -inf makes the sum inf or NaN) the wave
+    // takes the slow path: raise the reference to the true running maximum, rescale l and
+    // O, and form the probabilities again.  Values up to 2^8 lose nothing in fp32 sums or in
+    // 16-bit P, and the final normalisation divides by the true sum, so the result is the
+    // same function; the common tile needs neither a row maximum nor a rescale.
+    auto mask = [&](f32x16(&s)[QB][KT], int k0) __attribute__((always_inline)) {  // keys past the end, and keys after the query
         const bool need_mask = (k0 + BN > N) || (CAUSAL && (k0 + BN - 1 > qw0));
         if (need_mask) {
 #pragma unroll
@@ -323,34 +381,10 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
                     }
             }
         }
-
-        // online softmax (per query = per lane column), P^T packed as B operand.
-        // The reference maximum m_use is only raised when the tile maximum exceeds it by
-        // more than tau (2^8 in probability units): P may then be as large as 2^8, which
-        // fp32 sums and 16-bit P hold without loss, and the O accumulators are rescaled
-        // only on those rare tiles.  The final normalisation divides by the true sum, so
-        // the result is the same function.
-        u32x4 pk[QB][KT][2];
+    };
+    auto exp_pack = [&](const f32x16(&s)[QB][KT], u32x4(&pk)[QB][KT][2], float(&rs)[QB]) __attribute__((always_inline)) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-            float mx = s[qb][0][0];
-#pragma unroll
-            for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[qb][kt][v]);
-            mx = xhalf_max(mx);
-            if (__builtin_amdgcn_ballot_w64(mx > m_use[qb] + p.tau_raw) != 0) {  // wave-uniform
-                const float m_new = fmaxf(m_use[qb], mx);
-                // m_new is finite (key 0 is visible to every query and lives in tile 0);
-                // on the first tile m_use is -inf and alpha = exp2(-inf) = 0
-                const float alpha = __builtin_amdgcn_exp2f((m_use[qb] - m_new) * p.scale_l2);
-                m_use[qb] = m_new;
-                l_run[qb] *= alpha;
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) o[qb][dt][v] *= alpha;
-            }
             const float mb = m_use[qb] * p.scale_l2;
             float rs0 = 0.f, rs1 = 0.f;  // row sum of the unrounded probabilities, fp32
 #pragma unroll
@@ -369,47 +403,154 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
                     pk[qb][kt][t] = w;
                 }
             }
-            l_run[qb] += rs0 + rs1;
+            rs[qb] = rs0 + rs1;
         }
+    };
+    auto raise_reference = [&](const f32x16(&s)[QB][KT]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            float mx = s[qb][0][0];
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[qb][kt][v]);
+            const float m_new = fmaxf(m_use[qb], xhalf_max(mx));
+            // m_new is finite: key 0 is visible to every query and lives in tile 0, the first
+            // tile every wave processes.  There m_use = -inf and alpha = exp2(-inf) = 0.
+            const float alpha = __builtin_amdgcn_exp2f((m_use[qb] - m_new) * p.scale_l2);
+            m_use[qb] = m_new;
+            l_run[qb] *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[qb][dt][v] *= alpha;
+        }
+    };
+    auto softmax_tile = [&](f32x16(&s)[QB][KT], u32x4(&pk)[QB][KT][2], int k0) __attribute__((always_inline)) {
+        mask(s, k0);
+        float rs[QB];
+        exp_pack(s, pk, rs);
+        bool ok = true;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) ok = ok && (rs[qb] <= 256.0f);  // false for inf and NaN too
+        if (__builtin_amdgcn_ballot_w64(!ok) != 0) {                    // wave-uniform, rare
+            raise_reference(s);
+            exp_pack(s, pk, rs);
+        }
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) l_run[qb] += rs[qb];
+    };
 
-        // O^T += V^T . P^T
-        // k-slot s of step (kt, t) for lane group g is key kt*32 + 16*t + 8*(s/4) + 4*g + s%4
-#pragma unroll
-        for (int kt = 0; kt < KT; ++kt) {
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    const char* base = vb + (kt * 32 + 16 * t) * RB + voff[dt];
-                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(base));
-                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(base + 8 * RB));
-                    const u32x2 lo2 = __builtin_bit_cast(u32x2, lo);
-                    const u32x2 hi2 = __builtin_bit_cast(u32x2, hi);
-                    const u32x4 a = {lo2[0], lo2[1], hi2[0], hi2[1]};
-#pragma unroll
-                    for (int qb = 0; qb < QB; ++qb) o[qb][dt] = T::mfma(a, pk[qb][kt][t], o[qb][dt]);
+    constexpr std::integral_constant<int, 0> c0{};
+    constexpr std::integral_constant<int, 1> c1{};
+    constexpr std::true_type yes{};
+    constexpr std::false_type no{};
+    f32x16 s[QB][KT];
+    u32x4 pk[QB][KT][2];
+
+    if constexpr (PIPE == 0) {
+        // Plain order: every tile is loaded one iteration ahead; per tile S, softmax, PV.
+        // Overlap of MFMA and VALU work comes from the other waves resident on the SIMD.
+        auto step = [&](auto buf_c, int j) __attribute__((always_inline)) {
+            constexpr int BUF = decltype(buf_c)::value;
+            issue_k(j + 1, BUF ^ 1);
+            issue_v(j + 1, BUF ^ 1);
+            if (tile_active(j)) {
+                mfma_stream(no, yes, buf_c, buf_c, pk, s);
+                softmax_tile(s, pk, j * BN);
+                mfma_stream(yes, no, buf_c, buf_c, pk, s);
+            }
+            land_loads(BUF ^ 1);
+            __syncthreads();
+        };
+        issue_k(0, 0);
+        issue_v(0, 0);
+        land_loads(0);
+        __syncthreads();
+        for (int j = 0; j < nkt; j += 2) {
+            step(c0, j);
+            if (j + 1 < nkt) step(c1, j + 1);
+        }
+    } else {
+        // Ping-pong order for two waves per SIMD.  The tile loop is cut into two clusters:
+        //     M_j : O += P(j) V(j)  and  S(j+1) = K(j+1) Q^T      (MFMA + LDS reads only)
+        //     V_j : mask, softmax of S(j+1) -> P(j+1)              (VALU only)
+        // and the workgroup into two groups of NW/2 waves (waves w and w + NW/2 share a
+        // SIMD).  Group B runs one cluster behind group A, with a workgroup barrier between
+        // clusters ("slots"), so in every slot one wave of each SIMD feeds the MFMA pipe
+        // while the other one uses the VALU:
+        //     slot   0    1    2    3   ...
+        //     A      M_0  V_0  M_1  V_1
+        //     B      -    M_0  V_0  M_1
+        // S lives in registers from M to V, P from V to the next M; no second S buffer.
+        // LDS: M_j reads K(j+1) from K buffer (j+1)&1 and V(j) from V buffer j&1.  The loads
+        // of K(j+2) and V(j+1) are issued by every wave at the start of slot 2j (their
+        // targets were last read in slot 2j-1) and awaited at the end of slot 2j+1.
+        static_assert(LDP == 1, "the ping-pong order uses direct global->LDS loads");
+        static_assert(NW == 8, "the ping-pong order needs two waves per SIMD in one workgroup");
+        const bool grp_b = wave >= NW / 2;
+        auto slot_loads = [&](int j) __attribute__((always_inline)) {  // the loads of slot 2j; buffer indices are runtime here
+            issue_k(j + 2, j & 1);
+            issue_v(j + 1, (j + 1) & 1);
+        };
+        auto cluster_m = [&](auto par_c, int j) __attribute__((always_inline)) {  // par = j & 1
+            constexpr int PAR = decltype(par_c)::value;
+            constexpr std::integral_constant<int, PAR ^ 1> kbuf{};
+            // On a wave's last active tile the S part runs on a K buffer nobody needs (its
+            // result is dropped by cluster V): one code path instead of two keeps the
+            // accumulators in place.
+            if (tile_active(j)) mfma_stream(yes, yes, par_c, kbuf, pk, s);
+        };
+        auto cluster_v = [&](int j) __attribute__((always_inline)) {
+            if (tile_active(j + 1)) softmax_tile(s, pk, (j + 1) * BN);
+        };
+        auto wait_loads = [&]() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+
+        issue_k(0, 0);
+        issue_v(0, 0);
+        issue_k(1, 1);
+        wait_loads();
+        __syncthreads();
+        mfma_stream(no, yes, c0, c0, pk, s);
+        softmax_tile(s, pk, 0);
+        __syncthreads();  // every wave has read K(0) before K(2) overwrites it
+        if (!grp_b) {
+            for (int j = 0; j < nkt; j += 2) {
+                slot_loads(j);
+                cluster_m(c0, j);
+                __syncthreads();
+                cluster_v(j);
+                wait_loads();
+                __syncthreads();
+                if (j + 1 < nkt) {
+                    slot_loads(j + 1);
+                    cluster_m(c1, j + 1);
+                    __syncthreads();
+                    cluster_v(j + 1);
+                    wait_loads();
+                    __syncthreads();
+                }
+            }
+        } else {
+            slot_loads(0);
+            __syncthreads();
+            for (int j = 0; j < nkt; j += 2) {
+                cluster_m(c0, j);
+                wait_loads();
+                __syncthreads();
+                if (j + 1 < nkt) slot_loads(j + 1);
+                cluster_v(j);
+                if (j + 1 < nkt) {
+                    __syncthreads();
+                    cluster_m(c1, j + 1);
+                    wait_loads();
+                    __syncthreads();
+                    if (j + 2 < nkt) slot_loads(j + 2);
+                    cluster_v(j + 1);
+                    if (j + 2 < nkt) __syncthreads();
                 }
             }
         }
-    };
-
-    auto step = [&](auto buf_c, int j) {
-        constexpr int BUF = decltype(buf_c)::value;
-        const int k0 = j * BN;
-        const bool more = (j + 1 < nkt);
-        if (more) issue_loads(k0 + BN, BUF ^ 1);
-        // causal: a wave whose queries all precede this tile has nothing to compute
-        if (!CAUSAL || (k0 <= qw0 + 32 * QB - 1)) compute_tile(buf_c, k0);
-        if (more) land_loads(BUF ^ 1);
-        __syncthreads();
-    };
-
-    issue_loads(0, 0);
-    land_loads(0);
-    __syncthreads();
-    for (int j = 0; j < nkt; j += 2) {
-        step(std::integral_constant<int, 0>{}, j);
-        if (j + 1 < nkt) step(std::integral_constant<int, 1>{}, j + 1);
     }
 
     // ---- epilogue: normalise, round once, store O and lse
