@@ -284,12 +284,13 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
     };
     auto issue_k = [&](int j, int buf) __attribute__((always_inline)) { issue_tile(Kh, goffK0, j, smem_b + buf * 2 * TILE_BYTES, kst); };
     auto issue_v = [&](int j, int buf) __attribute__((always_inline)) { issue_tile(Vh, goffV0, j, smem_b + buf * 2 * TILE_BYTES + TILE_BYTES, vst); };
-    auto land_loads = [&](int buf) __attribute__((always_inline)) {  // make the tiles issued last visible in LDS to this thread
+    // make the tiles issued last visible in LDS to this thread (K into buffer kbuf, V into vbuf)
+    auto land_loads = [&](int kbuf, int vbuf) __attribute__((always_inline)) {
         if constexpr (LDP == 1) {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         } else {
-            char* kb = smem_b + buf * 2 * TILE_BYTES;
-            char* vb = kb + TILE_BYTES;
+            char* kb = smem_b + kbuf * 2 * TILE_BYTES;
+            char* vb = smem_b + vbuf * 2 * TILE_BYTES + TILE_BYTES;
 #pragma unroll
             for (int i = 0; i < LD_PER_THREAD; ++i) {
                 *reinterpret_cast<u32x4*>(kb + (i * NT + tid) * 16) = kst[i];
@@ -460,12 +461,12 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
                 softmax_tile(s, pk, j * BN);
                 mfma_stream(yes, no, buf_c, buf_c, pk, s);
             }
-            land_loads(BUF ^ 1);
+            land_loads(BUF ^ 1, BUF ^ 1);
             __syncthreads();
         };
         issue_k(0, 0);
         issue_v(0, 0);
-        land_loads(0);
+        land_loads(0, 0);
         __syncthreads();
         for (int j = 0; j < nkt; j += 2) {
             step(c0, j);
@@ -484,9 +485,11 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
         //     B      -    M_0  V_0  M_1
         // S lives in registers from M to V, P from V to the next M; no second S buffer.
         // LDS: M_j reads K(j+1) from K buffer (j+1)&1 and V(j) from V buffer j&1.  The loads
-        // of K(j+2) and V(j+1) are issued by every wave at the start of slot 2j (their
-        // targets were last read in slot 2j-1) and awaited at the end of slot 2j+1.
-        static_assert(LDP == 1, "the ping-pong order uses direct global->LDS loads");
+        // of K(j+2) and V(j+1) may start in slot 2j (their targets were last read in slot
+        // 2j-1) and must have landed when slot 2j+1 ends.  Every wave issues its share at
+        // the start of one of its V clusters (group B in slot 2j, group A in slot 2j+1):
+        // a wave that has LDS-direct loads in flight gets its own LDS reads queued behind
+        // them, which would stall an MFMA cluster but costs a VALU cluster nothing.
         static_assert(NW == 8, "the ping-pong order needs two waves per SIMD in one workgroup");
         const bool grp_b = wave >= NW / 2;
         auto slot_loads = [&](int j) __attribute__((always_inline)) {  // the loads of slot 2j; buffer indices are runtime here
@@ -504,30 +507,33 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
         auto cluster_v = [&](int j) __attribute__((always_inline)) {
             if (tile_active(j + 1)) softmax_tile(s, pk, (j + 1) * BN);
         };
-        auto wait_loads = [&]() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+        // lands what slot_loads(j) issued: K(j+2) -> K buffer j&1, V(j+1) -> V buffer (j+1)&1
+        auto land_slot = [&](int j) __attribute__((always_inline)) { land_loads(j & 1, (j + 1) & 1); };
 
         issue_k(0, 0);
         issue_v(0, 0);
+        land_loads(0, 0);
         issue_k(1, 1);
-        wait_loads();
+        if constexpr (LDP == 0) issue_v(1, 1);  // the staging path lands K and V together
+        land_loads(1, 1);
         __syncthreads();
         mfma_stream(no, yes, c0, c0, pk, s);
         softmax_tile(s, pk, 0);
         __syncthreads();  // every wave has read K(0) before K(2) overwrites it
         if (!grp_b) {
             for (int j = 0; j < nkt; j += 2) {
-                slot_loads(j);
                 cluster_m(c0, j);
                 __syncthreads();
+                slot_loads(j);
                 cluster_v(j);
-                wait_loads();
+                land_slot(j);
                 __syncthreads();
                 if (j + 1 < nkt) {
-                    slot_loads(j + 1);
                     cluster_m(c1, j + 1);
                     __syncthreads();
+                    slot_loads(j + 1);
                     cluster_v(j + 1);
-                    wait_loads();
+                    land_slot(j + 1);
                     __syncthreads();
                 }
             }
@@ -536,14 +542,14 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
             __syncthreads();
             for (int j = 0; j < nkt; j += 2) {
                 cluster_m(c0, j);
-                wait_loads();
+                land_slot(j);
                 __syncthreads();
                 if (j + 1 < nkt) slot_loads(j + 1);
                 cluster_v(j);
                 if (j + 1 < nkt) {
                     __syncthreads();
                     cluster_m(c1, j + 1);
-                    wait_loads();
+                    land_slot(j + 1);
                     __syncthreads();
                     if (j + 2 < nkt) slot_loads(j + 2);
                     cluster_v(j + 1);
