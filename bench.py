@@ -21,6 +21,13 @@ if ROOT not in sys.path:
 
 MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16/fp16 MFMA peak (published)
 
+# HBM bytes per launch of the default variant, from `rocprofv3 --pmc FETCH_SIZE` and
+# `--pmc WRITE_SIZE` runs scaled by the same counters on a 256 MiB device copy (FETCH_SIZE
+# counts 2 KiB, WRITE_SIZE 1 KiB); the runs and numbers are written up under profiles/.
+MEASURED_HBM_BYTES = {
+    "cfg2": (101936 * 2.0 + 73549.6 * 1.0) * 1024,
+}
+
 
 def device_tensors(w, seed):
     import numpy as np
@@ -54,6 +61,19 @@ def time_steps(A, w, tensors, variant, warmup, steps):
     return (t1 - t0) / steps, e0.elapsed_time(e1) * 1e-3 / steps
 
 
+def calibrate_copy(nbytes=256 << 20, reps=5):
+    """A plain device-to-device copy of known size, for scaling the FETCH_SIZE / WRITE_SIZE
+    counters of a `rocprofv3 --pmc` run (it reads nbytes and writes nbytes per launch)."""
+    import torch
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(reps):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"calibrate_copy_bytes": nbytes, "launches": reps}), flush=True)
+
+
 def cpu_baseline(w, bits, out, lse, budget_s=15.0):
     """The oracle as it stands, timed on this machine's host cores on a bounded row sample
     of the same workload; also returns the GPU-vs-oracle error on that sample."""
@@ -67,12 +87,14 @@ def cpu_baseline(w, bits, out, lse, budget_s=15.0):
         vis = (i + 1) if w.causal else np.full_like(i, w.N)
         return float(np.sum(4.0 * w.d * vis))
 
-    probe = I.sample_rows(w, 64, seed=99)
+    # size the sample from a probe that is large enough to amortise the per-head decode
+    total_rows = w.B * w.H * w.N
+    nprobe = min(total_rows, 4096)
+    probe = I.sample_rows(w, nprobe, seed=99)
     t0 = time.perf_counter()
     ref.attn_ref(qb, kb, vb, w.causal, w.scale, w.dtype, rows=probe)
     t_probe = max(time.perf_counter() - t0, 1e-4)
-    total_rows = w.B * w.H * w.N
-    n = int(min(total_rows, max(64, 64 * budget_s / t_probe)))
+    n = int(min(total_rows, max(nprobe, nprobe * budget_s / t_probe)))
     rows = I.sample_rows(w, n, seed=100)
     t0 = time.perf_counter()
     O_ref, l_ref, threads = ref.attn_ref(qb, kb, vb, w.causal, w.scale, w.dtype, rows=rows)
@@ -93,12 +115,14 @@ def cpu_baseline(w, bits, out, lse, budget_s=15.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=2, help="index into the benchmark configs (default 2)")
     ap.add_argument("--variant", type=int, default=None, help="schedule variant id (default: library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all", action="store_true", help="also time the other configs (reported under 'others')")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a 256 MiB device copy (counter calibration for rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
@@ -109,6 +133,9 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        calibrate_copy()
+        return
 
     w = I.WORKLOADS[args.workload]
     bits, tensors = device_tensors(w, seed=args.workload)
@@ -126,7 +153,8 @@ def main():
                    "variant": variant, "variant_desc": A.attn_variant_desc(variant),
                    "pct_of_mfma_peak": 100.0 * tflops / MFMA_PEAK_TFLOPS},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": None},
+                     "frac": achieved / MFMA_PEAK_TFLOPS,
+                     "traffic": MEASURED_HBM_BYTES.get(w.name) if args.variant is None else None},
     }
     if not args.no_cpu_baseline:
         base, parity = cpu_baseline(w, bits, tensors[3], tensors[4])
