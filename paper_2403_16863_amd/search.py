@@ -1,0 +1,280 @@
+"""Stochastic schedule search over the kernel's variant lattice.
+
+Follows the paper's method (Sec. 3 and Alg. 1) with compile-time schedule variants in
+place of perturbed machine code:
+
+* search space (Sec. 3.1): the lattice of knob vectors the library was built with;
+* mutation (Sec. 3.2): pick one coordinate at random and move it up or down by one;
+* feedback (Sec. 3.3, Eq. 1): R = (T_{i-1} - T_i) / T_0 from event-timed runs after a
+  warm-up; Energy(x) = T(x) / T_0, so that Delta E = -R;
+* search (Alg. 1): simulated annealing, geometric cooling T <- T / L, accept if
+  Delta E < 0, else with probability exp(-Delta E / T); the best schedule is only
+  updated on the Delta E < 0 branch;
+* testing (Sec. 4.2): before a variant is timed it is run on random inputs and compared
+  with the reference output of the unmodified (default) variant; a variant that fails is
+  never accepted;
+* offline use (Sec. 4.1): every visited candidate is stored, candidates are ranked
+  greedily by measured time and the best admitted one is reported.
+
+The annealing loop itself (`anneal`) is plain host logic over callables, so it can be
+exercised without a GPU.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import random
+import statistics
+from dataclasses import asdict, dataclass, field
+from typing import Callable, Dict, List, Optional, Sequence, Tuple
+
+Coords = Tuple[int, ...]
+
+
+# ----------------------------------------------------------------------------- lattice
+
+@dataclass
+class Lattice:
+    """Knob sizes plus the set of lattice points that hold a usable variant."""
+    sizes: Tuple[int, ...]
+    points: Dict[Coords, int]            # coords -> variant id
+
+    @staticmethod
+    def from_library(d: int, dtype: int, causal: bool) -> "Lattice":
+        from . import binding as B
+        sizes = tuple(B.attn_knob_size(k) for k in range(B.attn_num_knobs()))
+        pts = {}
+        for v in range(B.attn_num_variants()):
+            if B.attn_variant_supported(v, d, dtype, causal):
+                pts[tuple(B.attn_variant_coords(v))] = v
+        return Lattice(sizes, pts)
+
+
+def mutate(lat: Lattice, x: Coords, rng: random.Random, max_tries: int = 10000) -> Optional[Coords]:
+    """One move of the mutation policy: coordinate c ~ U{0..k-1}, direction +-1.  Moves that
+    leave the lattice or land on a point without a variant are redrawn; None if x has no
+    neighbour at all.  The returned action is encoded in the new coordinates."""
+    k = len(lat.sizes)
+    has_neighbour = any(
+        tuple(x[:c] + (x[c] + s,) + x[c + 1:]) in lat.points for c in range(k) for s in (-1, 1))
+    if not has_neighbour:
+        return None
+    for _ in range(max_tries):
+        c = rng.randrange(k)
+        s = rng.choice((-1, 1))
+        y = tuple(x[:c] + (x[c] + s,) + x[c + 1:])
+        if 0 <= y[c] < lat.sizes[c] and y in lat.points:
+            return y
+    return None
+
+
+# --------------------------------------------------------------------------- annealing
+
+@dataclass
+class Step:
+    step: int
+    temperature: float
+    x: Coords                 # schedule before the move
+    candidate: Coords
+    admitted: bool
+    t_candidate: Optional[float]   # runtime of the candidate (ms), None if not admitted
+    feedback: Optional[float]      # R of Eq. 1
+    delta_e: Optional[float]
+    accepted: bool
+    best: Coords
+
+
+@dataclass
+class SearchResult:
+    seed: int
+    t0: float
+    x0: Coords
+    best: Coords
+    t_best: float
+    final: Coords
+    t_final: float
+    steps: List[Step] = field(default_factory=list)
+    times: Dict[Coords, float] = field(default_factory=dict)       # every admitted candidate
+    rejected: List[Coords] = field(default_factory=list)           # failed admission
+
+    def ranking(self) -> List[Tuple[Coords, float]]:
+        """All admitted candidates, fastest first."""
+        return sorted(self.times.items(), key=lambda kv: kv[1])
+
+
+def anneal(lat: Lattice, x0: Coords, measure: Callable[[Coords], float],
+           admit: Callable[[Coords], bool], seed: int = 0, t_max: float = 0.05,
+           t_min: float = 5e-4, cool: float = 1.05, remeasure: bool = False,
+           log: Optional[Callable[[Step], None]] = None) -> SearchResult:
+    """Simulated annealing of Alg. 1.  `measure(x)` returns a runtime (any unit), `admit(x)`
+    says whether x passed the probabilistic test.  x0 must be admitted."""
+    if x0 not in lat.points:
+        raise ValueError("x0 is not a point of the lattice")
+    if not (t_max > t_min > 0 and cool > 1):
+        raise ValueError("need t_max > t_min > 0 and cool > 1")
+    rng = random.Random(seed)
+    if not admit(x0):
+        raise ValueError("the initial schedule fails its own admission test")
+    t0 = float(measure(x0))
+    times: Dict[Coords, float] = {x0: t0}
+    admitted: Dict[Coords, bool] = {x0: True}
+    res = SearchResult(seed=seed, t0=t0, x0=x0, best=x0, t_best=t0, final=x0, t_final=t0, times=times)
+
+    def energy(t: float) -> float:
+        return t / t0
+
+    x, t_x = x0, t0
+    best, t_best = x0, t0
+    temp = t_max
+    n = 0
+    while temp > t_min:
+        cand = mutate(lat, x, rng)
+        if cand is None:
+            break
+        if cand not in admitted:
+            admitted[cand] = bool(admit(cand))
+            if not admitted[cand]:
+                res.rejected.append(cand)
+        ok = admitted[cand]
+        accepted = False
+        t_c = fb = de = None
+        r = rng.random()                       # drawn every step: the trajectory depends on the seed only
+        if ok:
+            if remeasure or cand not in times:
+                times[cand] = float(measure(cand))
+            t_c = times[cand]
+            fb = (t_x - t_c) / t0              # Eq. 1
+            de = energy(t_c) - energy(t_x)     # = -fb
+            if de < 0:
+                accepted = True
+                x, t_x = cand, t_c
+                if energy(t_x) < energy(t_best):
+                    best, t_best = x, t_x
+            elif r < math.exp(-de / temp):
+                accepted = True
+                x, t_x = cand, t_c
+        st = Step(n, temp, res.final, cand, ok, t_c, fb, de, accepted, best)
+        res.steps.append(st)
+        res.final, res.t_final = x, t_x
+        if log:
+            log(st)
+        temp /= cool
+        n += 1
+    res.best, res.t_best = best, t_best
+    return res
+
+
+# ------------------------------------------------------------------ GPU-side callables
+
+def _device_inputs(B: int, H: int, N: int, d: int, dtype: int, seed: int, sigma: float = 1.0):
+    import torch
+    tdt = torch.float16 if dtype == 0 else torch.bfloat16
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    mk = lambda s: (torch.randn(B, H, N, d, device="cuda", generator=g) * s).to(tdt)
+    return mk(sigma), mk(sigma), mk(1.0)
+
+
+def admit_against_default(variant: int, d: int, dtype: int, causal: bool, samples: int = 16,
+                          seed: int = 0) -> bool:
+    """Probabilistic test of Sec. 4.2: random tensors, reference output from the default
+    variant, mismatch -> not admitted.  Shapes include ragged tails; the tolerance is the
+    library's accuracy contract (the variants round P and O alike, so they agree far
+    inside it)."""
+    import torch
+    from . import binding as Bd
+    tol_o = 1e-2 if dtype == 0 else 3e-2
+    rng = random.Random(seed)
+    shapes = [(1, 2, 1), (1, 1, 17), (2, 2, 127), (1, 2, 129), (1, 3, 1000), (2, 2, 384), (1, 4, 2048)]
+    for s in range(samples):
+        Bsz, H, N = shapes[s % len(shapes)]
+        sigma = rng.choice((1.0, 1.0, 2.0))
+        q, k, v = _device_inputs(Bsz, H, N, d, dtype, rng.randrange(1 << 30), sigma)
+        scale = 1.0 / math.sqrt(d)
+        ref_o = torch.empty_like(q)
+        ref_l = torch.empty(q.shape[:3], dtype=torch.float32, device="cuda")
+        default = Bd.attn_default_variant(N, d, dtype, causal)
+        Bd.attn_fwd_variant(q, k, v, ref_o, ref_l, causal, scale, default)
+        out = torch.full_like(q, float("nan"))
+        lse = torch.full_like(ref_l, float("nan"))
+        Bd.attn_fwd_variant(q, k, v, out, lse, causal, scale, variant)
+        torch.cuda.synchronize()
+        if not (torch.isfinite(out).all() and torch.isfinite(lse).all()):
+            return False
+        if (out.float() - ref_o.float()).abs().max().item() > tol_o:
+            return False
+        if ((lse - ref_l).abs() / ref_l.abs().clamp(min=1.0)).max().item() > 1e-3:
+            return False
+    return True
+
+
+def measure_variant(tensors, causal: bool, scale: float, variant: int, warmup: int = 10,
+                    iters: int = 50) -> float:
+    """Median of per-launch HIP-event times (ms) after a warm-up."""
+    from . import binding as Bd
+    q, k, v, out, lse = tensors
+    ms = Bd.attn_time_variant(q, k, v, out, lse, causal, scale, variant, warmup, iters)
+    return statistics.median(ms)
+
+
+def search_workload(widx: int, seed: int = 0, t_max: float = 0.05, t_min: float = 5e-4,
+                    cool: float = 1.05, samples: int = 16, db_path: Optional[str] = None,
+                    verbose: bool = False) -> dict:
+    """Run the annealing search on one of the benchmark workloads and report the best
+    admitted variant next to the library default."""
+    import torch
+    from . import binding as Bd
+    from . import inputs as I
+    w = I.WORKLOADS[widx]
+    lat = Lattice.from_library(w.d, w.dtype, w.causal)
+    q, k, v = _device_inputs(w.B, w.H, w.N, w.d, w.dtype, 1234 + widx, w.qk_sigma)
+    out = torch.empty_like(q)
+    lse = torch.empty(q.shape[:3], dtype=torch.float32, device="cuda")
+    tensors = (q, k, v, out, lse)
+    default = Bd.attn_default_variant(w.N, w.d, w.dtype, w.causal)
+    x0 = tuple(Bd.attn_variant_coords(default))
+    db = open(db_path, "a") if db_path else None
+
+    def log(st: Step):
+        rec = {"workload": w.name, "seed": seed, **asdict(st)}
+        if db:
+            db.write(json.dumps(rec) + "\n")
+            db.flush()
+        if verbose:
+            print(json.dumps(rec), flush=True)
+
+    res = anneal(lat, x0,
+                 measure=lambda c: measure_variant(tensors, w.causal, w.scale, lat.points[c]),
+                 admit=lambda c: admit_against_default(lat.points[c], w.d, w.dtype, w.causal, samples, seed),
+                 seed=seed, t_max=t_max, t_min=t_min, cool=cool, log=log)
+    if db:
+        db.close()
+    rank = res.ranking()
+    return {
+        "workload": w.label, "seed": seed, "steps": len(res.steps),
+        "default_variant": default, "default_desc": Bd.attn_variant_desc(default), "default_ms": res.t0,
+        "best_variant": lat.points[res.best], "best_desc": Bd.attn_variant_desc(lat.points[res.best]),
+        "best_ms": res.t_best, "gain_over_default": res.t0 / res.t_best,
+        "visited": len(res.times), "rejected": [lat.points[c] for c in res.rejected],
+        "ranking": [{"variant": lat.points[c], "ms": t} for c, t in rank],
+        "paper_context": "A100 speed-ups reported by the paper: 1.062x (attention), 1.123x (GEMM+LeakyReLU)",
+    }
+
+
+def main(argv: Optional[Sequence[str]] = None) -> None:
+    ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
+    ap.add_argument("--workload", type=int, default=2)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--tmax", type=float, default=0.05)
+    ap.add_argument("--tmin", type=float, default=5e-4)
+    ap.add_argument("--cool", type=float, default=1.05)
+    ap.add_argument("--samples", type=int, default=16, help="random inputs per admission test")
+    ap.add_argument("--db", type=str, default=None, help="append every step as JSON lines to this file")
+    ap.add_argument("--verbose", action="store_true")
+    a = ap.parse_args(argv)
+    print(json.dumps(search_workload(a.workload, a.seed, a.tmax, a.tmin, a.cool, a.samples, a.db, a.verbose)))
+
+
+if __name__ == "__main__":
+    main()
