@@ -132,6 +132,7 @@ int launch(const void* q, const void* k, const void* v, void* out, float* lse, i
     p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
     p.scale = scale > 0.f ? scale : (scale < 0.f ? -scale : 1.0f);
     p.scale_l2 = p.scale * 1.44269504088896340736f;
+    p.order = 1;
     // The launch's own return code is used (not hipGetLastError, which can report a
     // stale, unrelated status left behind by another library's earlier call).
     void* args[] = {&p};

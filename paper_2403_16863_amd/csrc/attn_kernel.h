@@ -55,6 +55,7 @@ struct Params {
     int total_wg;     // nqt * B * H
     float scale;      // multiplies q'.k, always > 0 (see qmode)
     float scale_l2;   // scale * log2(e)
+    int order;        // 1: tile-major order of an XCD's workgroups when its share is whole heads
     int qmode;        // 0: q' = q;  1: q' = -q (caller's scale was negative);
                       // 2: q' = 0 (caller's scale was zero, kernel runs with scale 1)
 };
@@ -168,8 +169,25 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
         const int base = p.total_wg >> 3, rem = p.total_wg & 7;
         logical = (xcd < rem ? xcd * (base + 1) : rem * (base + 1) + (xcd - rem) * base) + slot;
     }
-    const int bh = logical / p.nqt;
-    const int qt = p.nqt - 1 - (logical - bh * p.nqt);
+    // Inside an XCD's run of ids: the XCD's heads side by side, heaviest query tiles first
+    // (the last workgroups to start are then the lightest ones, whatever the head).
+    int bh, qt;
+    {
+        const int base = p.total_wg >> 3, rem = p.total_wg & 7;
+        const int xcd = blockIdx.x & 7;
+        const int first = xcd < rem ? xcd * (base + 1) : rem * (base + 1) + (xcd - rem) * base;
+        const int count = base + (xcd < rem ? 1 : 0);
+        const int h_lo = first / p.nqt, h_hi = (first + count - 1) / p.nqt;  // heads this XCD touches
+        const int nh = h_hi - h_lo + 1;
+        if (p.order == 1 && first % p.nqt == 0 && count % p.nqt == 0) {
+            const int r = logical - first;  // 0 .. count-1, count = nh * nqt
+            bh = h_lo + r % nh;
+            qt = p.nqt - 1 - r / nh;
+        } else {
+            bh = logical / p.nqt;
+            qt = p.nqt - 1 - (logical - bh * p.nqt);
+        }
+    }
     const int N = p.N;
     const int q0 = qt * BM;
     const int qw0 = q0 + wave * (32 * QB);  // first query row of this wave
@@ -373,13 +391,14 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
             for (int qb = 0; qb < QB; ++qb) {
                 const int qi = qw0 + qb * 32 + c;
                 const int lim = CAUSAL ? min(qi, N - 1) : N - 1;  // last visible key
+                // register v of sub-tile kt holds key k0 + kt*32 + 8*(v/4) + 4*g + v%4: compare
+                // the compile-time part with one per-lane value
+                const int rel = lim - k0 - 4 * g;
 #pragma unroll
                 for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int key = k0 + kt * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                        if (key > lim) s[qb][kt][v] = -INFINITY;
-                    }
+                    for (int v = 0; v < 16; ++v)
+                        if (kt * 32 + 8 * (v >> 2) + (v & 3) > rel) s[qb][kt][v] = -INFINITY;
             }
         }
     };
@@ -438,6 +457,16 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
             raise_reference(s);
             exp_pack(s, pk, rs);
         }
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) l_run[qb] += rs[qb];
+    };
+
+    // Tile 0 always takes the slow path (m_use = -inf): go there directly.
+    auto softmax_first_tile = [&](f32x16(&s)[QB][KT], u32x4(&pk)[QB][KT][2]) __attribute__((always_inline)) {
+        mask(s, 0);
+        float rs[QB];
+        raise_reference(s);
+        exp_pack(s, pk, rs);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) l_run[qb] += rs[qb];
     };
@@ -512,13 +541,18 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
 
         issue_k(0, 0);
         issue_v(0, 0);
-        land_loads(0, 0);
-        issue_k(1, 1);
-        if constexpr (LDP == 0) issue_v(1, 1);  // the staging path lands K and V together
-        land_loads(1, 1);
+        if constexpr (LDP == 1) {
+            issue_k(1, 1);  // all three first tiles in flight together, one wait
+            land_loads(0, 0);
+        } else {
+            land_loads(0, 0);
+            issue_k(1, 1);
+            issue_v(1, 1);  // the staging path lands K and V together
+            land_loads(1, 1);
+        }
         __syncthreads();
         mfma_stream(no, yes, c0, c0, pk, s);
-        softmax_tile(s, pk, 0);
+        softmax_first_tile(s, pk);
         __syncthreads();  // every wave has read K(0) before K(2) overwrites it
         if (!grp_b) {
             for (int j = 0; j < nkt; j += 2) {
