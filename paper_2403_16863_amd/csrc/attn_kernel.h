@@ -91,6 +91,27 @@ __device__ __forceinline__ void swap_halves(float x, float& lo_vals, float& hi_v
     lo_vals = a;
     hi_vals = b;
 }
+// Direct global -> LDS load of 16 bytes per lane: lane l reads  base + voff  and the
+// data lands at LDS address  lds_base + 16*l.  base and lds_base are wave-uniform and
+// travel in scalar registers, the per-lane part is one 32-bit VGPR that the caller
+// keeps for the whole kernel.  Written out by hand so that consecutive loads share no
+// address VGPR: with a freshly computed 64-bit VGPR address per load, the VALU write of
+// the next address has to wait until the previous load has left the issue queue.
+__device__ __forceinline__ void load_to_lds_16(const char* base, unsigned voff, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(base), "s"(lds_base) : "memory", "m0");
+}
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+    return (unsigned)(unsigned long)(const __attribute__((address_space(3))) char*)p;
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), unrolled at compile time
+template <int N, int I = 0, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<N, I + 1>(f);
+    }
+}
 __device__ __forceinline__ float xhalf_sum(float x) {
     float a, b;
     swap_halves(x, a, b);
@@ -253,52 +274,54 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
     // pk, qreg ...) by reference, and a call that is not inlined would push those arrays
     // out of registers into scratch memory.
 
-    // ---- K/V tile movement.  Thread t moves chunks  i*NT + t  (i < LD_PER_THREAD) of the
-    // physical LDS tile.  NT is a multiple of 256, so step i advances by a whole number of
-    // swizzle periods and the matching logical chunk in the row-major global tile is
-    //     goff0 + i * ROWS_PER_STEP * RB      (goff0 per lane, the rest compile-time).
-    static_assert(NT % 256 == 0, "load mapping assumes whole swizzle periods per step");
-    constexpr int ROWS_PER_STEP = NT / CPR;
-    unsigned goffK0, goffV0;
-    {
-        const int Lk = k_swz(tid);
-        goffK0 = (unsigned)((Lk / CPR) * RB + (Lk % CPR) * 16);
-        const int rowv = tid / CPR, pc = tid % CPR;
-        goffV0 = (unsigned)(rowv * RB + ((v_swz_slot<D>(rowv, pc >> 1) << 1) | (pc & 1)) * 16);
-    }
+    // ---- K/V tile movement.  A tile is moved by LNT loader threads (the whole workgroup,
+    // or one wave group of it): loader thread t moves chunks  i*LNT + t  (i < TILE_CHUNKS /
+    // LNT) of the physical LDS tile.  LNT is a multiple of 256, so piece i advances by a
+    // whole number of swizzle periods and the matching logical chunk in the row-major
+    // global tile is   goff0 + i * (LNT / CPR) * RB   (goff0 per lane, the rest compile-time).
+    auto goff_k = [&](int lt) __attribute__((always_inline)) {
+        const int Lk = k_swz(lt);
+        return (unsigned)((Lk / CPR) * RB + (Lk % CPR) * 16);
+    };
+    auto goff_v = [&](int lt) __attribute__((always_inline)) {
+        const int rowv = lt / CPR, pc = lt % CPR;
+        return (unsigned)(rowv * RB + ((v_swz_slot<D>(rowv, pc >> 1) << 1) | (pc & 1)) * 16);
+    };
+    const unsigned goffK0 = goff_k(tid), goffV0 = goff_v(tid);
     u32x4 kst[LDP == 0 ? LD_PER_THREAD : 1], vst[LDP == 0 ? LD_PER_THREAD : 1];
 
-    // One tile = LD_PER_THREAD steps; the source of step i is a wave-uniform base (tile
-    // start + i * ROWS_PER_STEP rows) plus the per-lane 32-bit offset.  The tile index is
-    // clamped to the last tile (a redundant reload into a buffer nobody reads any more is
-    // cheaper than a branch in every iteration).  Only the last, ragged tile takes the
-    // slow path, where rows past the end of the sequence are redirected to the last row
-    // (their scores are masked, so only finiteness of what is loaded matters).
-    auto issue_tile = [&](const char* head, unsigned goff0, int j, char* lds_tile, u32x4(&stage)[LDP == 0 ? LD_PER_THREAD : 1]) __attribute__((always_inline)) {
+    // Piece i of tile j: the source is a wave-uniform base (tile start + i * LNT / CPR rows)
+    // plus the per-lane 32-bit offset.  The tile index is clamped to the last tile (a
+    // redundant reload into a buffer nobody reads any more is cheaper than a branch in
+    // every iteration).  Only the last, ragged tile takes the slow path, where rows past
+    // the end of the sequence are redirected to the last row (their scores are masked, so
+    // only finiteness of what is loaded matters).
+    auto issue_piece = [&](auto lnt_c, const char* head, unsigned goff0, int lwave, int j, char* lds_tile, int i,
+                           u32x4& stage) __attribute__((always_inline)) {
+        constexpr int LNT = decltype(lnt_c)::value;
+        static_assert(LNT % 256 == 0 && TILE_CHUNKS % LNT == 0, "load mapping assumes whole swizzle periods per piece");
+        constexpr int ROWS_PER_PIECE = LNT / CPR;
         const int kt0 = min(j, nkt - 1) * BN;
+        char* dst = lds_tile + (i * LNT + lwave * 64) * 16;
         if (kt0 + BN <= N) {
-            const char* tb = head + (size_t)kt0 * RB;
-#pragma unroll
-            for (int i = 0; i < LD_PER_THREAD; ++i) {
-                const char* src = tb + (size_t)(i * ROWS_PER_STEP * RB) + goff0;
-                if constexpr (LDP == 1)
-                    __builtin_amdgcn_global_load_lds((global_void_ptr)src, (lds_void_ptr)(lds_tile + (i * NT + wave * 64) * 16), 16, 0, 0);
-                else
-                    stage[i] = *reinterpret_cast<const u32x4*>(src);
-            }
+            const char* pb = head + (size_t)kt0 * RB + (size_t)(i * ROWS_PER_PIECE * RB);
+            if constexpr (LDP == 1)
+                load_to_lds_16(pb, goff0, lds_address(dst));
+            else
+                stage = *reinterpret_cast<const u32x4*>(pb + goff0);
         } else {
-            const int row0 = (int)(goff0 / RB);
-            const unsigned col = goff0 % RB;
-#pragma unroll
-            for (int i = 0; i < LD_PER_THREAD; ++i) {
-                const int r = min(kt0 + row0 + i * ROWS_PER_STEP, N - 1);
-                const char* src = head + (size_t)r * RB + col;
-                if constexpr (LDP == 1)
-                    __builtin_amdgcn_global_load_lds((global_void_ptr)src, (lds_void_ptr)(lds_tile + (i * NT + wave * 64) * 16), 16, 0, 0);
-                else
-                    stage[i] = *reinterpret_cast<const u32x4*>(src);
-            }
+            const int r = min(kt0 + (int)(goff0 / RB) + i * ROWS_PER_PIECE, N - 1);
+            const char* src = head + (size_t)r * RB + goff0 % RB;
+            if constexpr (LDP == 1)
+                __builtin_amdgcn_global_load_lds((global_void_ptr)src, (lds_void_ptr)dst, 16, 0, 0);
+            else
+                stage = *reinterpret_cast<const u32x4*>(src);
         }
+    };
+    auto issue_tile = [&](const char* head, unsigned goff0, int j, char* lds_tile, u32x4(&stage)[LDP == 0 ? LD_PER_THREAD : 1]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < LD_PER_THREAD; ++i)
+            issue_piece(std::integral_constant<int, NT>{}, head, goff0, wave, j, lds_tile, i, stage[LDP == 0 ? i : 0]);
     };
     auto issue_k = [&](int j, int buf) __attribute__((always_inline)) { issue_tile(Kh, goffK0, j, smem_b + buf * 2 * TILE_BYTES, kst); };
     auto issue_v = [&](int j, int buf) __attribute__((always_inline)) { issue_tile(Vh, goffV0, j, smem_b + buf * 2 * TILE_BYTES + TILE_BYTES, vst); };
@@ -403,28 +426,25 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
         }
     };
     auto exp_pack = [&](const f32x16(&s)[QB][KT], u32x4(&pk)[QB][KT][2], float(&rs)[QB]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
+        static_for<QB>([&](auto qb_c) __attribute__((always_inline)) {
+            constexpr int qb = decltype(qb_c)::value;
             const float mb = m_use[qb] * p.scale_l2;
             float rs0 = 0.f, rs1 = 0.f;  // row sum of the unrounded probabilities, fp32
-#pragma unroll
-            for (int kt = 0; kt < KT; ++kt) {
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    u32x4 w;
-#pragma unroll
-                    for (int h = 0; h < 4; ++h) {
-                        const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][kt][8 * t + 2 * h], p.scale_l2, -mb));
-                        const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][kt][8 * t + 2 * h + 1], p.scale_l2, -mb));
-                        w[h] = T::pack2(e0, e1);
-                        rs0 += e0;
-                        rs1 += e1;
-                    }
-                    pk[qb][kt][t] = w;
-                }
-            }
+            static_for<KT * 2>([&](auto kk_c) __attribute__((always_inline)) {
+                constexpr int kt = decltype(kk_c)::value / 2, t = decltype(kk_c)::value % 2;
+                u32x4 w;
+                static_for<4>([&](auto h_c) __attribute__((always_inline)) {
+                    constexpr int h = decltype(h_c)::value;
+                    const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][kt][8 * t + 2 * h], p.scale_l2, -mb));
+                    const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][kt][8 * t + 2 * h + 1], p.scale_l2, -mb));
+                    w[h] = T::pack2(e0, e1);
+                    rs0 += e0;
+                    rs1 += e1;
+                });
+                pk[qb][kt][t] = w;
+            });
             rs[qb] = rs0 + rs1;
-        }
+        });
     };
     auto raise_reference = [&](const f32x16(&s)[QB][KT]) __attribute__((always_inline)) {
 #pragma unroll
@@ -521,10 +541,6 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
         // them, which would stall an MFMA cluster but costs a VALU cluster nothing.
         static_assert(NW == 8, "the ping-pong order needs two waves per SIMD in one workgroup");
         const bool grp_b = wave >= NW / 2;
-        auto slot_loads = [&](int j) __attribute__((always_inline)) {  // the loads of slot 2j; buffer indices are runtime here
-            issue_k(j + 2, j & 1);
-            issue_v(j + 1, (j + 1) & 1);
-        };
         auto cluster_m = [&](auto par_c, int j) __attribute__((always_inline)) {  // par = j & 1
             constexpr int PAR = decltype(par_c)::value;
             constexpr std::integral_constant<int, PAR ^ 1> kbuf{};
@@ -533,11 +549,6 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
             // accumulators in place.
             if (tile_active(j)) mfma_stream(yes, yes, par_c, kbuf, pk, s);
         };
-        auto cluster_v = [&](int j) __attribute__((always_inline)) {
-            if (tile_active(j + 1)) softmax_tile(s, pk, (j + 1) * BN);
-        };
-        // lands what slot_loads(j) issued: K(j+2) -> K buffer j&1, V(j+1) -> V buffer (j+1)&1
-        auto land_slot = [&](int j) __attribute__((always_inline)) { land_loads(j & 1, (j + 1) & 1); };
 
         issue_k(0, 0);
         issue_v(0, 0);
@@ -554,40 +565,54 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
         mfma_stream(no, yes, c0, c0, pk, s);
         softmax_first_tile(s, pk);
         __syncthreads();  // every wave has read K(0) before K(2) overwrites it
-        if (!grp_b) {
-            for (int j = 0; j < nkt; j += 2) {
-                cluster_m(c0, j);
-                __syncthreads();
-                slot_loads(j);
-                cluster_v(j);
-                land_slot(j);
-                __syncthreads();
-                if (j + 1 < nkt) {
-                    cluster_m(c1, j + 1);
+
+        {
+            // Every wave issues its share of a tile at the start of one of its V clusters
+            // (group B in slot 2j, group A in slot 2j+1).
+            auto slot_loads = [&](int j) __attribute__((always_inline)) {  // the loads of slot 2j; buffer indices are runtime here
+                issue_k(j + 2, j & 1);
+                issue_v(j + 1, (j + 1) & 1);
+            };
+            auto cluster_v = [&](int j) __attribute__((always_inline)) {
+                if (tile_active(j + 1)) softmax_tile(s, pk, (j + 1) * BN);
+            };
+            // lands what slot_loads(j) issued: K(j+2) -> K buffer j&1, V(j+1) -> V buffer (j+1)&1
+            auto land_slot = [&](int j) __attribute__((always_inline)) { land_loads(j & 1, (j + 1) & 1); };
+            if (!grp_b) {
+                for (int j = 0; j < nkt; j += 2) {
+                    cluster_m(c0, j);
                     __syncthreads();
-                    slot_loads(j + 1);
-                    cluster_v(j + 1);
-                    land_slot(j + 1);
+                    slot_loads(j);
+                    cluster_v(j);
+                    land_slot(j);
                     __syncthreads();
+                    if (j + 1 < nkt) {
+                        cluster_m(c1, j + 1);
+                        __syncthreads();
+                        slot_loads(j + 1);
+                        cluster_v(j + 1);
+                        land_slot(j + 1);
+                        __syncthreads();
+                    }
                 }
-            }
-        } else {
-            slot_loads(0);
-            __syncthreads();
-            for (int j = 0; j < nkt; j += 2) {
-                cluster_m(c0, j);
-                land_slot(j);
+            } else {
+                slot_loads(0);
                 __syncthreads();
-                if (j + 1 < nkt) slot_loads(j + 1);
-                cluster_v(j);
-                if (j + 1 < nkt) {
+                for (int j = 0; j < nkt; j += 2) {
+                    cluster_m(c0, j);
+                    land_slot(j);
                     __syncthreads();
-                    cluster_m(c1, j + 1);
-                    land_slot(j + 1);
-                    __syncthreads();
-                    if (j + 2 < nkt) slot_loads(j + 2);
-                    cluster_v(j + 1);
-                    if (j + 2 < nkt) __syncthreads();
+                    if (j + 1 < nkt) slot_loads(j + 1);
+                    cluster_v(j);
+                    if (j + 1 < nkt) {
+                        __syncthreads();
+                        cluster_m(c1, j + 1);
+                        land_slot(j + 1);
+                        __syncthreads();
+                        if (j + 2 < nkt) slot_loads(j + 2);
+                        cluster_v(j + 1);
+                        if (j + 2 < nkt) __syncthreads();
+                    }
                 }
             }
         }
