@@ -23,9 +23,9 @@ struct Variant {
 };
 
 // Knob value lists (lattice axes): bn {32,64,128}  nw {4,8}  qb {1,2}  occ {1,2}  ldp {0,1}
-// pipe {0,1}  pf {2,4,6,8}  prio {0,1}
+// pipe {0,1,2}  pf {2,4,6,8}  prio {0,1}
 const char* const kKnobNames[] = {"bn", "nw", "qb", "occ", "ldp", "pipe", "pf", "prio"};
-const int kKnobSizes[] = {3, 2, 2, 2, 2, 2, 4, 2};
+const int kKnobSizes[] = {3, 2, 2, 2, 2, 3, 4, 2};
 constexpr int kNumKnobs = 8;
 
 #define ATTN_KN(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO) attn::Knobs<BN, NW, QB, OCC, LDP, PIPE, PF, PRIO>
@@ -55,6 +55,11 @@ constexpr int kNumKnobs = 8;
      {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), IDX_OCC(OCC), LDP, PIPE, IDX_PF(PF), PRIO},               \
      {ATTN_KERNELS_FOR(64, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO), ATTN_NO_KERNELS}}
 
+#define VARIANT_D128(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)                                          \
+    {BN, NW, QB, OCC, LDP, PIPE, PF, PRIO,                                                          \
+     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), IDX_OCC(OCC), LDP, PIPE, IDX_PF(PF), PRIO},               \
+     {ATTN_NO_KERNELS, ATTN_KERNELS_FOR(128, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)}}
+
 const Variant kVariants[] = {
     VARIANT_BOTH(64, 4, 1, 2, 1, 0, 4, 0),   // 0: the hand-written default
     VARIANT_BOTH(64, 4, 1, 2, 1, 0, 2, 0),
@@ -71,8 +76,23 @@ const Variant kVariants[] = {
     VARIANT_BOTH(64, 8, 1, 1, 0, 1, 4, 0),
     VARIANT_BOTH(64, 4, 2, 1, 1, 0, 4, 0),
     VARIANT_D64(128, 4, 1, 2, 1, 0, 4, 0),
+    VARIANT_D128(64, 8, 1, 1, 1, 2, 2, 1),   // 15, 16: MFMA work in both ping-pong clusters
+    VARIANT_D128(64, 8, 1, 1, 1, 2, 4, 1),
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
+
+// Compute units of the current device (queried once per device).
+int cu_count() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
 
 bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
@@ -125,6 +145,7 @@ int launch(const void* q, const void* k, const void* v, void* out, float* lse, i
     p.H = H;
     p.N = N;
     p.nqt = (int)nqt;
+    p.BH = B * H;
     p.total_wg = (int)total;
     // The kernel tracks the running maximum of the raw dot products, which needs a
     // positive multiplier: a negative scale is moved into the sign of Q, a zero scale
@@ -132,13 +153,21 @@ int launch(const void* q, const void* k, const void* v, void* out, float* lse, i
     p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
     p.scale = scale > 0.f ? scale : (scale < 0.f ? -scale : 1.0f);
     p.scale_l2 = p.scale * 1.44269504088896340736f;
-    p.order = 1;
+    // Persistent workgroups: as many as the device keeps resident (occ per CU), a multiple
+    // of 8 when every XCD can be given whole heads, never more than there are work items.
+    p.order = 2;
+    const long long resident = (long long)cu_count() * var.occ;
+    long long grid = total < resident ? total : resident;
+    if ((p.BH & 7) == 0 && (resident & 7) == 0) {
+        const long long per_xcd_items = (long long)(p.BH >> 3) * nqt, per_xcd_wg = resident >> 3;
+        grid = 8 * (per_xcd_items < per_xcd_wg ? per_xcd_items : per_xcd_wg);
+    }
     // The launch's own return code is used (not hipGetLastError, which can report a
     // stale, unrelated status left behind by another library's earlier call).
     void* args[] = {&p};
-    const hipError_t e = hipLaunchKernel((const void*)fn, dim3((unsigned)total), dim3(var.nw * 64),
+    const hipError_t e = hipLaunchKernel((const void*)fn, dim3((unsigned)grid), dim3(var.nw * 64),
                                          args, 0, (hipStream_t)stream);
-    if (e != hipSuccess) fprintf(stderr, "attn: hipLaunchKernel failed: %s (%d), grid=%lld block=%d\n", hipGetErrorString(e), (int)e, total, var.nw * 64);
+    if (e != hipSuccess) fprintf(stderr, "attn: hipLaunchKernel failed: %s (%d), grid=%lld block=%d\n", hipGetErrorString(e), (int)e, grid, var.nw * 64);
     return e == hipSuccess ? ATTN_OK : ATTN_ELAUNCH;
 }
 

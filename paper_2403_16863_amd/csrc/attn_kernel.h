@@ -52,10 +52,15 @@ struct Params {
     float* lse;
     int H, N;
     int nqt;          // query tiles per head
-    int total_wg;     // nqt * B * H
+    int BH;           // B * H
+    int total_wg;     // nqt * B * H = number of work items (one query tile of one head each)
     float scale;      // multiplies q'.k, always > 0 (see qmode)
     float scale_l2;   // scale * log2(e)
-    int order;        // 1: tile-major order of an XCD's workgroups when its share is whole heads
+    int order;        // how work items reach workgroups:
+                      // 0, 1: one item per workgroup (grid = total_wg), each XCD a contiguous run of
+                      //       ids, inside a head (0) or across the XCD's heads (1) heaviest tile first;
+                      // 2: persistent workgroups (grid = resident workgroups), each takes the items
+                      //    of a fixed serpentine schedule one after the other
     int qmode;        // 0: q' = q;  1: q' = -q (caller's scale was negative);
                       // 2: q' = 0 (caller's scale was zero, kernel runs with scale 1)
 };
@@ -150,7 +155,8 @@ struct Knobs {
     static constexpr int OCC = OCC_;    // workgroups per CU the register budget aims for
     static constexpr int LDP = LDP_;    // K/V load path: 0 = through VGPRs, 1 = global -> LDS directly
     static constexpr int PIPE = PIPE_;  // 0 = per tile S, softmax, PV, waves run free;
-                                        // 1 = two-cluster ping-pong between the two waves of a SIMD
+                                        // 1 = two-cluster ping-pong between the two waves of a SIMD (MFMA | VALU),
+                                        // 2 = ping-pong with MFMA work in both clusters, softmax inside the PV MFMAs
     static constexpr int PF = PF_;      // LDS fragment prefetch distance of the MFMA streams, in MFMA steps
     static constexpr int PRIO = PRIO_;  // 1 = raise the wave priority (s_setprio) while it runs an MFMA stream
 };
@@ -181,26 +187,43 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
     const int g = lane >> 5;
     const int c = lane & 31;
 
-    // ---- workgroup -> (head, query tile).  Workgroups are dealt round-robin to the
-    // 8 XCDs; give each XCD a contiguous run of logical ids so that all query tiles
-    // of a head share one L2, and start with the heaviest (last) query tiles.
-    int logical;
-    {
+    // ---- work item (head, query tile) of this workgroup in a given round.
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: all query tiles
+    // of a head should run on one XCD, and the heaviest (last, under a causal mask) query
+    // tiles should start first.
+    auto item_of_round = [&](int round, int& bh, int& qt) __attribute__((always_inline)) -> bool {
+        if (p.order == 2) {
+            // Persistent: items sorted by weight (query tile descending, then head) are dealt
+            // to the G workgroups in serpentine order (0..G-1, G-1..0, ...), so the sums of
+            // linearly decreasing weights come out even.  With whole heads per XCD the deal
+            // runs inside each XCD over that XCD's heads (x, x+8, ...).
+            const int G = (int)gridDim.x, gidx = (int)blockIdx.x;
+            int r, nh, h0, hs;
+            if ((G & 7) == 0 && (p.BH & 7) == 0) {
+                const int C = G >> 3, cidx = gidx >> 3;
+                r = round * C + ((round & 1) ? C - 1 - cidx : cidx);
+                nh = p.BH >> 3, h0 = gidx & 7, hs = 8;
+            } else {
+                r = round * G + ((round & 1) ? G - 1 - gidx : gidx);
+                nh = p.BH, h0 = 0, hs = 1;
+            }
+            if (r >= nh * p.nqt) return false;
+            qt = p.nqt - 1 - r / nh;
+            bh = h0 + hs * (r % nh);
+            return true;
+        }
+        if (round > 0) return false;
+        // One item per workgroup: give each XCD a contiguous run of logical ids.
         const int bid = blockIdx.x, xcd = bid & 7, slot = bid >> 3;
         const int base = p.total_wg >> 3, rem = p.total_wg & 7;
-        logical = (xcd < rem ? xcd * (base + 1) : rem * (base + 1) + (xcd - rem) * base) + slot;
-    }
-    // Inside an XCD's run of ids: the XCD's heads side by side, heaviest query tiles first
-    // (the last workgroups to start are then the lightest ones, whatever the head).
-    int bh, qt;
-    {
-        const int base = p.total_wg >> 3, rem = p.total_wg & 7;
-        const int xcd = blockIdx.x & 7;
         const int first = xcd < rem ? xcd * (base + 1) : rem * (base + 1) + (xcd - rem) * base;
         const int count = base + (xcd < rem ? 1 : 0);
+        const int logical = first + slot;
         const int h_lo = first / p.nqt, h_hi = (first + count - 1) / p.nqt;  // heads this XCD touches
         const int nh = h_hi - h_lo + 1;
         if (p.order == 1 && first % p.nqt == 0 && count % p.nqt == 0) {
+            // the XCD's heads side by side, heaviest query tiles first (the last workgroups
+            // to start are then the lightest ones, whatever the head)
             const int r = logical - first;  // 0 .. count-1, count = nh * nqt
             bh = h_lo + r % nh;
             qt = p.nqt - 1 - r / nh;
@@ -208,434 +231,626 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
             bh = logical / p.nqt;
             qt = p.nqt - 1 - (logical - bh * p.nqt);
         }
-    }
+        return true;
+    };
     const int N = p.N;
-    const int q0 = qt * BM;
-    const int qw0 = q0 + wave * (32 * QB);  // first query row of this wave
-    const int qw_last = qw0 + 32 * QB - 1;  // causal: tile j is active for this wave iff j*BN <= qw_last
+    for (int round = 0;; ++round) {
+        int bh, qt;
+        if (!item_of_round(round, bh, qt)) break;
+        if (round > 0) __syncthreads();  // every wave is done with the previous item's tiles in LDS
+        const int q0 = qt * BM;
+        const int qw0 = q0 + wave * (32 * QB);  // first query row of this wave
+        const int qw_last = qw0 + 32 * QB - 1;  // causal: tile j is active for this wave iff j*BN <= qw_last
 
-    const size_t head_off = (size_t)bh * N * D;
-    const uint16_t* __restrict__ Qh = p.q + head_off;
-    const char* __restrict__ Kh = reinterpret_cast<const char*>(p.k + head_off);
-    const char* __restrict__ Vh = reinterpret_cast<const char*>(p.v + head_off);
+        const size_t head_off = (size_t)bh * N * D;
+        const uint16_t* __restrict__ Qh = p.q + head_off;
+        const char* __restrict__ Kh = reinterpret_cast<const char*>(p.k + head_off);
+        const char* __restrict__ Vh = reinterpret_cast<const char*>(p.v + head_off);
 
-    // ---- Q as B operand, resident in registers
-    u32x4 qreg[QB][KS];
+        // ---- Q as B operand, resident in registers.  Loaded after the first K/V tiles have
+        // been issued, so that the wait for Q (which every item reads exactly once, from
+        // HBM) does not delay them.
+        u32x4 qreg[QB][KS];
+        auto load_q = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const int row = qw0 + qb * 32 + c;
+            for (int qb = 0; qb < QB; ++qb) {
+                const int row = qw0 + qb * 32 + c;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            u32x4 val = {0, 0, 0, 0};
-            if (row < N && p.qmode != 2)
-                val = *reinterpret_cast<const u32x4*>(Qh + (size_t)row * D + ks * 16 + g * 8);
-            if (p.qmode == 1) val ^= 0x80008000u;  // flip the sign of all eight elements
-            qreg[qb][ks] = val;
+                for (int ks = 0; ks < KS; ++ks) {
+                    u32x4 val = {0, 0, 0, 0};
+                    if (row < N && p.qmode != 2)
+                        val = *reinterpret_cast<const u32x4*>(Qh + (size_t)row * D + ks * 16 + g * 8);
+                    if (p.qmode == 1) val ^= 0x80008000u;  // flip the sign of all eight elements
+                    qreg[qb][ks] = val;
+                }
+            }
+        };
+
+        f32x16 o[QB][DT];
+        float m_use[QB], l_run[QB];  // reference maximum in use (raw units), partial row sum
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            m_use[qb] = -INFINITY;
+            l_run[qb] = 0.f;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[qb][dt][v] = 0.f;
         }
-    }
 
-    f32x16 o[QB][DT];
-    float m_use[QB], l_run[QB];  // reference maximum in use (raw units), partial row sum
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        m_use[qb] = -INFINITY;
-        l_run[qb] = 0.f;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[qb][dt][v] = 0.f;
-    }
+        // key tiles this workgroup visits
+        const int kend = CAUSAL ? min(N, q0 + BM) : N;  // keys [0, kend)
+        const int nkt = (kend + BN - 1) / BN;
+        auto tile_active = [&](int j) __attribute__((always_inline)) { return j < nkt && (!CAUSAL || j * BN <= qw_last); };
 
-    // key tiles this workgroup visits
-    const int kend = CAUSAL ? min(N, q0 + BM) : N;  // keys [0, kend)
-    const int nkt = (kend + BN - 1) / BN;
-    auto tile_active = [&](int j) __attribute__((always_inline)) { return j < nkt && (!CAUSAL || j * BN <= qw_last); };
-
-    // ---- per-lane LDS read offsets (bytes inside one K or V tile), loop invariant.
-    // K: lane reads row (kt*32 + c), logical chunk (2*ks + g); moving kt by one adds
-    // 32 rows, which leaves the swizzle term unchanged, so kt is an immediate offset.
-    int koff[KS];
+        // ---- per-lane LDS read offsets (bytes inside one K or V tile), loop invariant.
+        // K: lane reads row (kt*32 + c), logical chunk (2*ks + g); moving kt by one adds
+        // 32 rows, which leaves the swizzle term unchanged, so kt is an immediate offset.
+        int koff[KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) koff[ks] = k_swz(c * CPR + 2 * ks + g) * 16;
-    // V: lane (16-lane group gq = lane/16, i = lane%16) addresses row 4*g + i/4 (+ 16*t + 8*hi
-    // + 32*kt, all multiples of 4, again immediates) and d column dt*32 + (gq&1)*16 + 4*(i%4).
-    int voff[DT];
-    {
-        const int i16 = lane & 15;
-        const int row = 4 * g + (i16 >> 2);
+        for (int ks = 0; ks < KS; ++ks) koff[ks] = k_swz(c * CPR + 2 * ks + g) * 16;
+        // V: lane (16-lane group gq = lane/16, i = lane%16) addresses row 4*g + i/4 (+ 16*t + 8*hi
+        // + 32*kt, all multiples of 4, again immediates) and d column dt*32 + (gq&1)*16 + 4*(i%4).
+        int voff[DT];
+        {
+            const int i16 = lane & 15;
+            const int row = 4 * g + (i16 >> 2);
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            const int dcol = dt * 32 + ((lane >> 4) & 1) * 16 + 4 * (i16 & 3);
-            voff[dt] = row * RB + v_swz_slot<D>(row, dcol >> 4) * 32 + (dcol & 15) * 2;
-        }
-    }
-
-    // All helper lambdas below are force-inlined: they capture the register arrays (o, s,
-    // pk, qreg ...) by reference, and a call that is not inlined would push those arrays
-    // out of registers into scratch memory.
-
-    // ---- K/V tile movement.  A tile is moved by LNT loader threads (the whole workgroup,
-    // or one wave group of it): loader thread t moves chunks  i*LNT + t  (i < TILE_CHUNKS /
-    // LNT) of the physical LDS tile.  LNT is a multiple of 256, so piece i advances by a
-    // whole number of swizzle periods and the matching logical chunk in the row-major
-    // global tile is   goff0 + i * (LNT / CPR) * RB   (goff0 per lane, the rest compile-time).
-    auto goff_k = [&](int lt) __attribute__((always_inline)) {
-        const int Lk = k_swz(lt);
-        return (unsigned)((Lk / CPR) * RB + (Lk % CPR) * 16);
-    };
-    auto goff_v = [&](int lt) __attribute__((always_inline)) {
-        const int rowv = lt / CPR, pc = lt % CPR;
-        return (unsigned)(rowv * RB + ((v_swz_slot<D>(rowv, pc >> 1) << 1) | (pc & 1)) * 16);
-    };
-    const unsigned goffK0 = goff_k(tid), goffV0 = goff_v(tid);
-    u32x4 kst[LDP == 0 ? LD_PER_THREAD : 1], vst[LDP == 0 ? LD_PER_THREAD : 1];
-
-    // Piece i of tile j: the source is a wave-uniform base (tile start + i * LNT / CPR rows)
-    // plus the per-lane 32-bit offset.  The tile index is clamped to the last tile (a
-    // redundant reload into a buffer nobody reads any more is cheaper than a branch in
-    // every iteration).  Only the last, ragged tile takes the slow path, where rows past
-    // the end of the sequence are redirected to the last row (their scores are masked, so
-    // only finiteness of what is loaded matters).
-    auto issue_piece = [&](auto lnt_c, const char* head, unsigned goff0, int lwave, int j, char* lds_tile, int i,
-                           u32x4& stage) __attribute__((always_inline)) {
-        constexpr int LNT = decltype(lnt_c)::value;
-        static_assert(LNT % 256 == 0 && TILE_CHUNKS % LNT == 0, "load mapping assumes whole swizzle periods per piece");
-        constexpr int ROWS_PER_PIECE = LNT / CPR;
-        const int kt0 = min(j, nkt - 1) * BN;
-        char* dst = lds_tile + (i * LNT + lwave * 64) * 16;
-        if (kt0 + BN <= N) {
-            const char* pb = head + (size_t)kt0 * RB + (size_t)(i * ROWS_PER_PIECE * RB);
-            if constexpr (LDP == 1)
-                load_to_lds_16(pb, goff0, lds_address(dst));
-            else
-                stage = *reinterpret_cast<const u32x4*>(pb + goff0);
-        } else {
-            const int r = min(kt0 + (int)(goff0 / RB) + i * ROWS_PER_PIECE, N - 1);
-            const char* src = head + (size_t)r * RB + goff0 % RB;
-            if constexpr (LDP == 1)
-                __builtin_amdgcn_global_load_lds((global_void_ptr)src, (lds_void_ptr)dst, 16, 0, 0);
-            else
-                stage = *reinterpret_cast<const u32x4*>(src);
-        }
-    };
-    auto issue_tile = [&](const char* head, unsigned goff0, int j, char* lds_tile, u32x4(&stage)[LDP == 0 ? LD_PER_THREAD : 1]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < LD_PER_THREAD; ++i)
-            issue_piece(std::integral_constant<int, NT>{}, head, goff0, wave, j, lds_tile, i, stage[LDP == 0 ? i : 0]);
-    };
-    auto issue_k = [&](int j, int buf) __attribute__((always_inline)) { issue_tile(Kh, goffK0, j, smem_b + buf * 2 * TILE_BYTES, kst); };
-    auto issue_v = [&](int j, int buf) __attribute__((always_inline)) { issue_tile(Vh, goffV0, j, smem_b + buf * 2 * TILE_BYTES + TILE_BYTES, vst); };
-    // make the tiles issued last visible in LDS to this thread (K into buffer kbuf, V into vbuf)
-    auto land_loads = [&](int kbuf, int vbuf) __attribute__((always_inline)) {
-        if constexpr (LDP == 1) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        } else {
-            char* kb = smem_b + kbuf * 2 * TILE_BYTES;
-            char* vb = smem_b + vbuf * 2 * TILE_BYTES + TILE_BYTES;
-#pragma unroll
-            for (int i = 0; i < LD_PER_THREAD; ++i) {
-                *reinterpret_cast<u32x4*>(kb + (i * NT + tid) * 16) = kst[i];
-                *reinterpret_cast<u32x4*>(vb + (i * NT + tid) * 16) = vst[i];
+            for (int dt = 0; dt < DT; ++dt) {
+                const int dcol = dt * 32 + ((lane >> 4) & 1) * 16 + 4 * (i16 & 3);
+                voff[dt] = row * RB + v_swz_slot<D>(row, dcol >> 4) * 32 + (dcol & 15) * 2;
             }
         }
-    };
 
-    // ---- MFMA work as a software-pipelined stream: NVF steps of O^T += V^T P^T (each needs
-    // one V fragment = two transposing reads; k-slot s of step (kt, t) for lane group g is
-    // key kt*32 + 16*t + 8*(s/4) + 4*g + s%4) and/or NKF steps of S^T = K Q^T (one 16-byte K
-    // fragment each, alternating between the KT independent accumulators).  Fragments are
-    // read PF steps ahead into a ring of registers, in source order pinned by scheduling
-    // fences, so an MFMA never waits for an LDS read issued just before it.  Buffer indices
-    // are compile-time constants so every LDS offset folds into the instruction.
-    auto mfma_stream = [&](auto has_pv_c, auto has_qk_c, auto vbuf_c, auto kbuf_c,
-                           const u32x4(&pk)[QB][KT][2], f32x16(&s)[QB][KT]) __attribute__((always_inline)) {
-        constexpr bool HAS_PV = decltype(has_pv_c)::value, HAS_QK = decltype(has_qk_c)::value;
-        constexpr int VB = decltype(vbuf_c)::value, KB = decltype(kbuf_c)::value;
-        constexpr int N0 = HAS_PV ? NVF : 0, NS = N0 + (HAS_QK ? NKF : 0);
-        const char* vb = smem_b + VB * 2 * TILE_BYTES + TILE_BYTES;
-        const char* kb = smem_b + KB * 2 * TILE_BYTES;
-        auto read_frag = [&](int i) __attribute__((always_inline)) -> u32x4 {
-            if (i < N0) {  // V fragment i = (kt*2 + t)*DT + dt
+        // All helper lambdas below are force-inlined: they capture the register arrays (o, s,
+        // pk, qreg ...) by reference, and a call that is not inlined would push those arrays
+        // out of registers into scratch memory.
+
+        // ---- K/V tile movement.  A tile is moved by LNT loader threads (the whole workgroup,
+        // or one wave group of it): loader thread t moves chunks  i*LNT + t  (i < TILE_CHUNKS /
+        // LNT) of the physical LDS tile.  LNT is a multiple of 256, so piece i advances by a
+        // whole number of swizzle periods and the matching logical chunk in the row-major
+        // global tile is   goff0 + i * (LNT / CPR) * RB   (goff0 per lane, the rest compile-time).
+        auto goff_k = [&](int lt) __attribute__((always_inline)) {
+            const int Lk = k_swz(lt);
+            return (unsigned)((Lk / CPR) * RB + (Lk % CPR) * 16);
+        };
+        auto goff_v = [&](int lt) __attribute__((always_inline)) {
+            const int rowv = lt / CPR, pc = lt % CPR;
+            return (unsigned)(rowv * RB + ((v_swz_slot<D>(rowv, pc >> 1) << 1) | (pc & 1)) * 16);
+        };
+        const unsigned goffK0 = goff_k(tid), goffV0 = goff_v(tid);
+        u32x4 kst[LDP == 0 ? LD_PER_THREAD : 1], vst[LDP == 0 ? LD_PER_THREAD : 1];
+
+        // Piece i of tile j: the source is a wave-uniform base (tile start + i * LNT / CPR rows)
+        // plus the per-lane 32-bit offset.  The tile index is clamped to the last tile (a
+        // redundant reload into a buffer nobody reads any more is cheaper than a branch in
+        // every iteration).  Only the last, ragged tile takes the slow path, where rows past
+        // the end of the sequence are redirected to the last row (their scores are masked, so
+        // only finiteness of what is loaded matters).
+        auto issue_piece = [&](auto lnt_c, const char* head, unsigned goff0, int lwave, int j, char* lds_tile, int i,
+                               u32x4& stage) __attribute__((always_inline)) {
+            constexpr int LNT = decltype(lnt_c)::value;
+            static_assert(LNT % 256 == 0 && TILE_CHUNKS % LNT == 0, "load mapping assumes whole swizzle periods per piece");
+            constexpr int ROWS_PER_PIECE = LNT / CPR;
+            const int kt0 = min(j, nkt - 1) * BN;
+            char* dst = lds_tile + (i * LNT + lwave * 64) * 16;
+            if (kt0 + BN <= N) {
+                const char* pb = head + (size_t)kt0 * RB + (size_t)(i * ROWS_PER_PIECE * RB);
+                if constexpr (LDP == 1)
+                    load_to_lds_16(pb, goff0, lds_address(dst));
+                else
+                    stage = *reinterpret_cast<const u32x4*>(pb + goff0);
+            } else {
+                const int r = min(kt0 + (int)(goff0 / RB) + i * ROWS_PER_PIECE, N - 1);
+                const char* src = head + (size_t)r * RB + goff0 % RB;
+                if constexpr (LDP == 1)
+                    __builtin_amdgcn_global_load_lds((global_void_ptr)src, (lds_void_ptr)dst, 16, 0, 0);
+                else
+                    stage = *reinterpret_cast<const u32x4*>(src);
+            }
+        };
+        auto issue_tile = [&](const char* head, unsigned goff0, int j, char* lds_tile, u32x4(&stage)[LDP == 0 ? LD_PER_THREAD : 1]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int i = 0; i < LD_PER_THREAD; ++i)
+                issue_piece(std::integral_constant<int, NT>{}, head, goff0, wave, j, lds_tile, i, stage[LDP == 0 ? i : 0]);
+        };
+        auto issue_k = [&](int j, int buf) __attribute__((always_inline)) { issue_tile(Kh, goffK0, j, smem_b + buf * 2 * TILE_BYTES, kst); };
+        auto issue_v = [&](int j, int buf) __attribute__((always_inline)) { issue_tile(Vh, goffV0, j, smem_b + buf * 2 * TILE_BYTES + TILE_BYTES, vst); };
+        // make the tiles issued last visible in LDS to this thread (K into buffer kbuf, V into vbuf)
+        auto land_loads = [&](int kbuf, int vbuf) __attribute__((always_inline)) {
+            if constexpr (LDP == 1) {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            } else {
+                char* kb = smem_b + kbuf * 2 * TILE_BYTES;
+                char* vb = smem_b + vbuf * 2 * TILE_BYTES + TILE_BYTES;
+#pragma unroll
+                for (int i = 0; i < LD_PER_THREAD; ++i) {
+                    *reinterpret_cast<u32x4*>(kb + (i * NT + tid) * 16) = kst[i];
+                    *reinterpret_cast<u32x4*>(vb + (i * NT + tid) * 16) = vst[i];
+                }
+            }
+        };
+
+        // ---- MFMA work as a software-pipelined stream: NVF steps of O^T += V^T P^T (each needs
+        // one V fragment = two transposing reads; k-slot s of step (kt, t) for lane group g is
+        // key kt*32 + 16*t + 8*(s/4) + 4*g + s%4) and/or NKF steps of S^T = K Q^T (one 16-byte K
+        // fragment each, alternating between the KT independent accumulators).  Fragments are
+        // read PF steps ahead into a ring of registers, in source order pinned by scheduling
+        // fences, so an MFMA never waits for an LDS read issued just before it.  Buffer indices
+        // are compile-time constants so every LDS offset folds into the instruction.
+        auto mfma_stream = [&](auto has_pv_c, auto has_qk_c, auto vbuf_c, auto kbuf_c,
+                               const u32x4(&pk)[QB][KT][2], f32x16(&s)[QB][KT]) __attribute__((always_inline)) {
+            constexpr bool HAS_PV = decltype(has_pv_c)::value, HAS_QK = decltype(has_qk_c)::value;
+            constexpr int VB = decltype(vbuf_c)::value, KB = decltype(kbuf_c)::value;
+            constexpr int N0 = HAS_PV ? NVF : 0, NS = N0 + (HAS_QK ? NKF : 0);
+            const char* vb = smem_b + VB * 2 * TILE_BYTES + TILE_BYTES;
+            const char* kb = smem_b + KB * 2 * TILE_BYTES;
+            auto read_frag = [&](int i) __attribute__((always_inline)) -> u32x4 {
+                if (i < N0) {  // V fragment i = (kt*2 + t)*DT + dt
+                    const int dt = i % DT, t = (i / DT) & 1, kt = i / (2 * DT);
+                    const char* base = vb + (kt * 32 + 16 * t) * RB + voff[dt];
+                    const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(base)));
+                    const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(base + 8 * RB)));
+                    return u32x4{lo[0], lo[1], hi[0], hi[1]};
+                } else {       // K fragment f = ks*KT + kt
+                    const int f = i - N0;
+                    return *reinterpret_cast<const u32x4*>(kb + (f % KT) * 32 * RB + koff[f / KT]);
+                }
+            };
+            if constexpr (HAS_QK) {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) s[qb][kt][v] = 0.f;
+            }
+            if constexpr (PRIO == 1) __builtin_amdgcn_s_setprio(2);
+            constexpr int NPRE = PF < NS ? PF : NS;
+            u32x4 ring[PF];
+#pragma unroll
+            for (int i = 0; i < NPRE; ++i) ring[i] = read_frag(i);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < NS; ++i) {
+                if (i < N0) {
+                    const int dt = i % DT, t = (i / DT) & 1, kt = i / (2 * DT);
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb) o[qb][dt] = T::mfma(ring[i % PF], pk[qb][kt][t], o[qb][dt]);
+                } else {
+                    const int f = i - N0, ks = f / KT, kt = f % KT;
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb) s[qb][kt] = T::mfma(ring[i % PF], qreg[qb][ks], s[qb][kt]);
+                }
+                if (i + PF < NS) ring[i % PF] = read_frag(i + PF);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if constexpr (PRIO == 1) __builtin_amdgcn_s_setprio(0);
+        };
+
+        // ---- softmax of one tile (per query = per lane column): S -> P^T packed as B operand.
+        //
+        // P = exp2(scale_l2 * (S - m_use)) with a reference maximum m_use that is NOT updated on
+        // every tile: the probabilities are first formed against the current reference, and
+        // only if a lane's partial row sum leaves [0, 2^8] (a score grew past the reference by a
+        // lot, or this is the first tile, where m_use = -inf makes the sum inf or NaN) the wave
+        // takes the slow path: raise the reference to the true running maximum, rescale l and
+        // O, and form the probabilities again.  Values up to 2^8 lose nothing in fp32 sums or in
+        // 16-bit P, and the final normalisation divides by the true sum, so the result is the
+        // same function; the common tile needs neither a row maximum nor a rescale.
+        auto mask = [&](f32x16(&s)[QB][KT], int k0) __attribute__((always_inline)) {  // keys past the end, and keys after the query
+            const bool need_mask = (k0 + BN > N) || (CAUSAL && (k0 + BN - 1 > qw0));
+            if (need_mask) {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    const int qi = qw0 + qb * 32 + c;
+                    const int lim = CAUSAL ? min(qi, N - 1) : N - 1;  // last visible key
+                    // register v of sub-tile kt holds key k0 + kt*32 + 8*(v/4) + 4*g + v%4: compare
+                    // the compile-time part with one per-lane value
+                    const int rel = lim - k0 - 4 * g;
+#pragma unroll
+                    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v)
+                            if (kt * 32 + 8 * (v >> 2) + (v & 3) > rel) s[qb][kt][v] = -INFINITY;
+                }
+            }
+        };
+        auto exp_pack = [&](const f32x16(&s)[QB][KT], u32x4(&pk)[QB][KT][2], float(&rs)[QB]) __attribute__((always_inline)) {
+            static_for<QB>([&](auto qb_c) __attribute__((always_inline)) {
+                constexpr int qb = decltype(qb_c)::value;
+                const float mb = m_use[qb] * p.scale_l2;
+                float rs0 = 0.f, rs1 = 0.f;  // row sum of the unrounded probabilities, fp32
+                static_for<KT * 2>([&](auto kk_c) __attribute__((always_inline)) {
+                    constexpr int kt = decltype(kk_c)::value / 2, t = decltype(kk_c)::value % 2;
+                    u32x4 w;
+                    static_for<4>([&](auto h_c) __attribute__((always_inline)) {
+                        constexpr int h = decltype(h_c)::value;
+                        const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][kt][8 * t + 2 * h], p.scale_l2, -mb));
+                        const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][kt][8 * t + 2 * h + 1], p.scale_l2, -mb));
+                        w[h] = T::pack2(e0, e1);
+                        rs0 += e0;
+                        rs1 += e1;
+                    });
+                    pk[qb][kt][t] = w;
+                });
+                rs[qb] = rs0 + rs1;
+            });
+        };
+        auto raise_reference = [&](const f32x16(&s)[QB][KT]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                float mx = s[qb][0][0];
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[qb][kt][v]);
+                const float m_new = fmaxf(m_use[qb], xhalf_max(mx));
+                // m_new is finite: key 0 is visible to every query and lives in tile 0, the first
+                // tile every wave processes.  There m_use = -inf and alpha = exp2(-inf) = 0.
+                const float alpha = __builtin_amdgcn_exp2f((m_use[qb] - m_new) * p.scale_l2);
+                m_use[qb] = m_new;
+                l_run[qb] *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) o[qb][dt][v] *= alpha;
+            }
+        };
+        auto softmax_tile = [&](f32x16(&s)[QB][KT], u32x4(&pk)[QB][KT][2], int k0) __attribute__((always_inline)) {
+            mask(s, k0);
+            float rs[QB];
+            exp_pack(s, pk, rs);
+            bool ok = true;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) ok = ok && (rs[qb] <= 256.0f);  // false for inf and NaN too
+            if (__builtin_amdgcn_ballot_w64(!ok) != 0) {                    // wave-uniform, rare
+                raise_reference(s);
+                exp_pack(s, pk, rs);
+            }
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) l_run[qb] += rs[qb];
+        };
+
+        // Tile 0 always takes the slow path (m_use = -inf): go there directly.
+        auto softmax_first_tile = [&](f32x16(&s)[QB][KT], u32x4(&pk)[QB][KT][2]) __attribute__((always_inline)) {
+            mask(s, 0);
+            float rs[QB];
+            raise_reference(s);
+            exp_pack(s, pk, rs);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) l_run[qb] += rs[qb];
+        };
+
+        // ---- O^T += V^T P^T for tile j with the softmax of tile j+1 worked into it: after
+        // each MFMA a few elements of S(j+1) go through scale, exp2, row sum and packing while
+        // the MFMA is in the pipe (a wave's own VALU instructions issue behind its MFMA).
+        // pk holds P(j) on entry and P(j+1) on exit: MFMA step i reads the vector pk[kt][t] with
+        // (kt*2 + t) = i / DT, and the pairs formed during the DT steps that read one vector
+        // make up exactly the new contents of that vector, which replace it after its last
+        // read.  Same arithmetic, element by element, as softmax_tile.
+        auto pv_softmax_stream = [&](auto vbuf_c, u32x4(&pk)[QB][KT][2], f32x16(&s)[QB][KT], int k0,
+                                     bool next_active) __attribute__((always_inline)) {
+            static_assert(QB == 1 && DT == 4, "pairing of MFMA steps and P vectors assumes one query block and d = 128");
+            constexpr int VB = decltype(vbuf_c)::value;
+            const char* vb = smem_b + VB * 2 * TILE_BYTES + TILE_BYTES;
+            auto read_v = [&](int i) __attribute__((always_inline)) -> u32x4 {  // V fragment i = (kt*2 + t)*DT + dt
                 const int dt = i % DT, t = (i / DT) & 1, kt = i / (2 * DT);
                 const char* base = vb + (kt * 32 + 16 * t) * RB + voff[dt];
                 const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(base)));
                 const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(base + 8 * RB)));
                 return u32x4{lo[0], lo[1], hi[0], hi[1]};
-            } else {       // K fragment f = ks*KT + kt
-                const int f = i - N0;
-                return *reinterpret_cast<const u32x4*>(kb + (f % KT) * 32 * RB + koff[f / KT]);
-            }
-        };
-        if constexpr (HAS_QK) {
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) s[qb][kt][v] = 0.f;
-        }
-        if constexpr (PRIO == 1) __builtin_amdgcn_s_setprio(2);
-        constexpr int NPRE = PF < NS ? PF : NS;
-        u32x4 ring[PF];
-#pragma unroll
-        for (int i = 0; i < NPRE; ++i) ring[i] = read_frag(i);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < NS; ++i) {
-            if (i < N0) {
-                const int dt = i % DT, t = (i / DT) & 1, kt = i / (2 * DT);
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) o[qb][dt] = T::mfma(ring[i % PF], pk[qb][kt][t], o[qb][dt]);
-            } else {
-                const int f = i - N0, ks = f / KT, kt = f % KT;
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) s[qb][kt] = T::mfma(ring[i % PF], qreg[qb][ks], s[qb][kt]);
-            }
-            if (i + PF < NS) ring[i % PF] = read_frag(i + PF);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if constexpr (PRIO == 1) __builtin_amdgcn_s_setprio(0);
-    };
-
-    // ---- softmax of one tile (per query = per lane column): S -> P^T packed as B operand.
-    //
-    // P = exp2(scale_l2 * (S - m_use)) with a reference maximum m_use that is NOT updated on
-    // every tile: the probabilities are first formed against the current reference, and
-    // only if a lane's partial row sum leaves [0, 2^8] (a score grew past the reference by a
-    // lot, or this is the first tile, where m_use = -inf makes the sum inf or NaN) the wave
-    // takes the slow path: raise the reference to the true running maximum, rescale l and
-    // O, and form the probabilities again.  Values up to 2^8 lose nothing in fp32 sums or in
-    // 16-bit P, and the final normalisation divides by the true sum, so the result is the
-    // same function; the common tile needs neither a row maximum nor a rescale.
-    auto mask = [&](f32x16(&s)[QB][KT], int k0) __attribute__((always_inline)) {  // keys past the end, and keys after the query
-        const bool need_mask = (k0 + BN > N) || (CAUSAL && (k0 + BN - 1 > qw0));
-        if (need_mask) {
+            };
+            mask(s, k0);
+            float mb[QB], rs0[QB], rs1[QB];
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
-                const int qi = qw0 + qb * 32 + c;
-                const int lim = CAUSAL ? min(qi, N - 1) : N - 1;  // last visible key
-                // register v of sub-tile kt holds key k0 + kt*32 + 8*(v/4) + 4*g + v%4: compare
-                // the compile-time part with one per-lane value
-                const int rel = lim - k0 - 4 * g;
-#pragma unroll
-                for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        if (kt * 32 + 8 * (v >> 2) + (v & 3) > rel) s[qb][kt][v] = -INFINITY;
+                mb[qb] = m_use[qb] * p.scale_l2;
+                rs0[qb] = 0.f;
+                rs1[qb] = 0.f;
             }
-        }
-    };
-    auto exp_pack = [&](const f32x16(&s)[QB][KT], u32x4(&pk)[QB][KT][2], float(&rs)[QB]) __attribute__((always_inline)) {
-        static_for<QB>([&](auto qb_c) __attribute__((always_inline)) {
-            constexpr int qb = decltype(qb_c)::value;
-            const float mb = m_use[qb] * p.scale_l2;
-            float rs0 = 0.f, rs1 = 0.f;  // row sum of the unrounded probabilities, fp32
-            static_for<KT * 2>([&](auto kk_c) __attribute__((always_inline)) {
-                constexpr int kt = decltype(kk_c)::value / 2, t = decltype(kk_c)::value % 2;
-                u32x4 w;
-                static_for<4>([&](auto h_c) __attribute__((always_inline)) {
-                    constexpr int h = decltype(h_c)::value;
-                    const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][kt][8 * t + 2 * h], p.scale_l2, -mb));
-                    const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][kt][8 * t + 2 * h + 1], p.scale_l2, -mb));
-                    w[h] = T::pack2(e0, e1);
-                    rs0 += e0;
-                    rs1 += e1;
-                });
-                pk[qb][kt][t] = w;
-            });
-            rs[qb] = rs0 + rs1;
-        });
-    };
-    auto raise_reference = [&](const f32x16(&s)[QB][KT]) __attribute__((always_inline)) {
+            if constexpr (PRIO == 1) __builtin_amdgcn_s_setprio(2);
+            constexpr int NPRE = PF < NVF ? PF : NVF;
+            u32x4 ring[PF];
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            float mx = s[qb][0][0];
+            for (int i = 0; i < NPRE; ++i) ring[i] = read_v(i);
+            __builtin_amdgcn_sched_barrier(0);
+            // Two-stage software pipeline over the MFMA steps: step i forms the exponentials of
+            // pair i+1 and packs / sums pair i, so the operations inside one step (which the
+            // fences keep together) do not wait for each other.
+            u32x4 w;
+            auto exp_pair = [&](int i, float& e0, float& e1) __attribute__((always_inline)) {
+                const int t = (i / DT) & 1, kt = i / (2 * DT), h = i % DT;
+                e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[0][kt][8 * t + 2 * h], p.scale_l2, -mb[0]));
+                e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[0][kt][8 * t + 2 * h + 1], p.scale_l2, -mb[0]));
+            };
+            float ea0, ea1, eb0, eb1;
+            exp_pair(0, ea0, ea1);
 #pragma unroll
-            for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[qb][kt][v]);
-            const float m_new = fmaxf(m_use[qb], xhalf_max(mx));
-            // m_new is finite: key 0 is visible to every query and lives in tile 0, the first
-            // tile every wave processes.  There m_use = -inf and alpha = exp2(-inf) = 0.
-            const float alpha = __builtin_amdgcn_exp2f((m_use[qb] - m_new) * p.scale_l2);
-            m_use[qb] = m_new;
-            l_run[qb] *= alpha;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) o[qb][dt][v] *= alpha;
-        }
-    };
-    auto softmax_tile = [&](f32x16(&s)[QB][KT], u32x4(&pk)[QB][KT][2], int k0) __attribute__((always_inline)) {
-        mask(s, k0);
-        float rs[QB];
-        exp_pack(s, pk, rs);
-        bool ok = true;
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) ok = ok && (rs[qb] <= 256.0f);  // false for inf and NaN too
-        if (__builtin_amdgcn_ballot_w64(!ok) != 0) {                    // wave-uniform, rare
-            raise_reference(s);
-            exp_pack(s, pk, rs);
-        }
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) l_run[qb] += rs[qb];
-    };
-
-    // Tile 0 always takes the slow path (m_use = -inf): go there directly.
-    auto softmax_first_tile = [&](f32x16(&s)[QB][KT], u32x4(&pk)[QB][KT][2]) __attribute__((always_inline)) {
-        mask(s, 0);
-        float rs[QB];
-        raise_reference(s);
-        exp_pack(s, pk, rs);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) l_run[qb] += rs[qb];
-    };
-
-    constexpr std::integral_constant<int, 0> c0{};
-    constexpr std::integral_constant<int, 1> c1{};
-    constexpr std::true_type yes{};
-    constexpr std::false_type no{};
-    f32x16 s[QB][KT];
-    u32x4 pk[QB][KT][2];
-
-    if constexpr (PIPE == 0) {
-        // Plain order: every tile is loaded one iteration ahead; per tile S, softmax, PV.
-        // Overlap of MFMA and VALU work comes from the other waves resident on the SIMD.
-        auto step = [&](auto buf_c, int j) __attribute__((always_inline)) {
-            constexpr int BUF = decltype(buf_c)::value;
-            issue_k(j + 1, BUF ^ 1);
-            issue_v(j + 1, BUF ^ 1);
-            if (tile_active(j)) {
-                mfma_stream(no, yes, buf_c, buf_c, pk, s);
-                softmax_tile(s, pk, j * BN);
-                mfma_stream(yes, no, buf_c, buf_c, pk, s);
+            for (int i = 0; i < NVF; ++i) {
+                const int dt = i % DT, t = (i / DT) & 1, kt = i / (2 * DT), h = i % DT;
+                o[0][dt] = T::mfma(ring[i % PF], pk[0][kt][t], o[0][dt]);
+                if (i + PF < NVF) ring[i % PF] = read_v(i + PF);
+                if (i + 1 < NVF) exp_pair(i + 1, eb0, eb1);
+                unsigned packed = T::pack2(ea0, ea1);
+                // pinned here: the slow path below overwrites P, so the compiler would otherwise
+                // sink the conversions into the fast path and keep every exponential alive
+                asm volatile("" : "+v"(packed));
+                w[h] = packed;
+                rs0[0] += ea0;
+                rs1[0] += ea1;
+                ea0 = eb0;
+                ea1 = eb1;
+                if (h == DT - 1) pk[0][kt][t] = w;  // all reads of the old vector have been issued
+                __builtin_amdgcn_sched_barrier(0);
             }
-            land_loads(BUF ^ 1, BUF ^ 1);
+            if constexpr (PRIO == 1) __builtin_amdgcn_s_setprio(0);
+            // On a wave's last active tile there is no S(j+1): the stream above still runs in
+            // full (a second, PV-only code path would make the register allocator move the
+            // O accumulators between the two), on stale scores whose results are dropped here.
+            // The row sums are consumed unconditionally (select, not branch): otherwise the
+            // compiler sinks the additions into the branch and keeps every exponential alive.
+            float rs[QB];
+            bool bad = false;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                rs[qb] = rs0[qb] + rs1[qb];
+                bad = bad || !(rs[qb] <= 256.0f);  // true for inf and NaN too
+            }
+            if (__builtin_amdgcn_ballot_w64(bad && next_active) != 0) {  // wave-uniform, rare
+                raise_reference(s);
+                exp_pack(s, pk, rs);
+            }
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) l_run[qb] += next_active ? rs[qb] : 0.f;
+        };
+
+        constexpr std::integral_constant<int, 0> c0{};
+        constexpr std::integral_constant<int, 1> c1{};
+        constexpr std::true_type yes{};
+        constexpr std::false_type no{};
+        f32x16 s[QB][KT];
+        u32x4 pk[QB][KT][2];
+
+        if constexpr (PIPE == 0) {
+            // Plain order: every tile is loaded one iteration ahead; per tile S, softmax, PV.
+            // Overlap of MFMA and VALU work comes from the other waves resident on the SIMD.
+            auto step = [&](auto buf_c, int j) __attribute__((always_inline)) {
+                constexpr int BUF = decltype(buf_c)::value;
+                issue_k(j + 1, BUF ^ 1);
+                issue_v(j + 1, BUF ^ 1);
+                if (tile_active(j)) {
+                    mfma_stream(no, yes, buf_c, buf_c, pk, s);
+                    softmax_tile(s, pk, j * BN);
+                    mfma_stream(yes, no, buf_c, buf_c, pk, s);
+                }
+                land_loads(BUF ^ 1, BUF ^ 1);
+                __syncthreads();
+            };
+            issue_k(0, 0);
+            issue_v(0, 0);
+            load_q();
+            land_loads(0, 0);
             __syncthreads();
-        };
-        issue_k(0, 0);
-        issue_v(0, 0);
-        land_loads(0, 0);
-        __syncthreads();
-        for (int j = 0; j < nkt; j += 2) {
-            step(c0, j);
-            if (j + 1 < nkt) step(c1, j + 1);
-        }
-    } else {
-        // Ping-pong order for two waves per SIMD.  The tile loop is cut into two clusters:
-        //     M_j : O += P(j) V(j)  and  S(j+1) = K(j+1) Q^T      (MFMA + LDS reads only)
-        //     V_j : mask, softmax of S(j+1) -> P(j+1)              (VALU only)
-        // and the workgroup into two groups of NW/2 waves (waves w and w + NW/2 share a
-        // SIMD).  Group B runs one cluster behind group A, with a workgroup barrier between
-        // clusters ("slots"), so in every slot one wave of each SIMD feeds the MFMA pipe
-        // while the other one uses the VALU:
-        //     slot   0    1    2    3   ...
-        //     A      M_0  V_0  M_1  V_1
-        //     B      -    M_0  V_0  M_1
-        // S lives in registers from M to V, P from V to the next M; no second S buffer.
-        // LDS: M_j reads K(j+1) from K buffer (j+1)&1 and V(j) from V buffer j&1.  The loads
-        // of K(j+2) and V(j+1) may start in slot 2j (their targets were last read in slot
-        // 2j-1) and must have landed when slot 2j+1 ends.  Every wave issues its share at
-        // the start of one of its V clusters (group B in slot 2j, group A in slot 2j+1):
-        // a wave that has LDS-direct loads in flight gets its own LDS reads queued behind
-        // them, which would stall an MFMA cluster but costs a VALU cluster nothing.
-        static_assert(NW == 8, "the ping-pong order needs two waves per SIMD in one workgroup");
-        const bool grp_b = wave >= NW / 2;
-        auto cluster_m = [&](auto par_c, int j) __attribute__((always_inline)) {  // par = j & 1
-            constexpr int PAR = decltype(par_c)::value;
-            constexpr std::integral_constant<int, PAR ^ 1> kbuf{};
-            // On a wave's last active tile the S part runs on a K buffer nobody needs (its
-            // result is dropped by cluster V): one code path instead of two keeps the
-            // accumulators in place.
-            if (tile_active(j)) mfma_stream(yes, yes, par_c, kbuf, pk, s);
-        };
-
-        issue_k(0, 0);
-        issue_v(0, 0);
-        if constexpr (LDP == 1) {
-            issue_k(1, 1);  // all three first tiles in flight together, one wait
-            land_loads(0, 0);
+            for (int j = 0; j < nkt; j += 2) {
+                step(c0, j);
+                if (j + 1 < nkt) step(c1, j + 1);
+            }
         } else {
-            land_loads(0, 0);
-            issue_k(1, 1);
-            issue_v(1, 1);  // the staging path lands K and V together
-            land_loads(1, 1);
-        }
-        __syncthreads();
-        mfma_stream(no, yes, c0, c0, pk, s);
-        softmax_first_tile(s, pk);
-        __syncthreads();  // every wave has read K(0) before K(2) overwrites it
+            // Ping-pong order for two waves per SIMD.  The tile loop is cut into two clusters:
+            //     M_j : O += P(j) V(j)  and  S(j+1) = K(j+1) Q^T      (MFMA + LDS reads only)
+            //     V_j : mask, softmax of S(j+1) -> P(j+1)              (VALU only)
+            // and the workgroup into two groups of NW/2 waves (waves w and w + NW/2 share a
+            // SIMD).  Group B runs one cluster behind group A, with a workgroup barrier between
+            // clusters ("slots"), so in every slot one wave of each SIMD feeds the MFMA pipe
+            // while the other one uses the VALU:
+            //     slot   0    1    2    3   ...
+            //     A      M_0  V_0  M_1  V_1
+            //     B      -    M_0  V_0  M_1
+            // S lives in registers from M to V, P from V to the next M; no second S buffer.
+            // LDS: M_j reads K(j+1) from K buffer (j+1)&1 and V(j) from V buffer j&1.  The loads
+            // of K(j+2) and V(j+1) may start in slot 2j (their targets were last read in slot
+            // 2j-1) and must have landed when slot 2j+1 ends.  Every wave issues its share at
+            // the start of one of its V clusters (group B in slot 2j, group A in slot 2j+1):
+            // a wave that has LDS-direct loads in flight gets its own LDS reads queued behind
+            // them, which would stall an MFMA cluster but costs a VALU cluster nothing.
+            static_assert(NW == 8, "the ping-pong order needs two waves per SIMD in one workgroup");
+            const bool grp_b = wave >= NW / 2;
+            auto cluster_m = [&](auto par_c, int j) __attribute__((always_inline)) {  // par = j & 1
+                constexpr int PAR = decltype(par_c)::value;
+                constexpr std::integral_constant<int, PAR ^ 1> kbuf{};
+                // On a wave's last active tile the S part runs on a K buffer nobody needs (its
+                // result is dropped by cluster V): one code path instead of two keeps the
+                // accumulators in place.
+                if (tile_active(j)) mfma_stream(yes, yes, par_c, kbuf, pk, s);
+            };
 
-        {
-            // Every wave issues its share of a tile at the start of one of its V clusters
-            // (group B in slot 2j, group A in slot 2j+1).
-            auto slot_loads = [&](int j) __attribute__((always_inline)) {  // the loads of slot 2j; buffer indices are runtime here
-                issue_k(j + 2, j & 1);
-                issue_v(j + 1, (j + 1) & 1);
-            };
-            auto cluster_v = [&](int j) __attribute__((always_inline)) {
-                if (tile_active(j + 1)) softmax_tile(s, pk, (j + 1) * BN);
-            };
-            // lands what slot_loads(j) issued: K(j+2) -> K buffer j&1, V(j+1) -> V buffer (j+1)&1
-            auto land_slot = [&](int j) __attribute__((always_inline)) { land_loads(j & 1, (j + 1) & 1); };
-            if (!grp_b) {
-                for (int j = 0; j < nkt; j += 2) {
-                    cluster_m(c0, j);
-                    __syncthreads();
-                    slot_loads(j);
-                    cluster_v(j);
-                    land_slot(j);
-                    __syncthreads();
-                    if (j + 1 < nkt) {
-                        cluster_m(c1, j + 1);
+            issue_k(0, 0);
+            issue_v(0, 0);
+            if constexpr (LDP == 1) {
+                issue_k(1, 1);  // all three first tiles in flight together, one wait
+                load_q();
+                land_loads(0, 0);
+            } else {
+                load_q();
+                land_loads(0, 0);
+                issue_k(1, 1);
+                issue_v(1, 1);  // the staging path lands K and V together
+                land_loads(1, 1);
+            }
+            __syncthreads();
+            mfma_stream(no, yes, c0, c0, pk, s);
+            softmax_first_tile(s, pk);
+            __syncthreads();  // every wave has read K(0) before K(2) overwrites it
+
+            if constexpr (PIPE == 1) {
+                // Every wave issues its share of a tile at the start of one of its V clusters
+                // (group B in slot 2j, group A in slot 2j+1).
+                auto slot_loads = [&](int j) __attribute__((always_inline)) {  // the loads of slot 2j; buffer indices are runtime here
+                    issue_k(j + 2, j & 1);
+                    issue_v(j + 1, (j + 1) & 1);
+                };
+                auto cluster_v = [&](int j) __attribute__((always_inline)) {
+                    if (tile_active(j + 1)) softmax_tile(s, pk, (j + 1) * BN);
+                };
+                // lands what slot_loads(j) issued: K(j+2) -> K buffer j&1, V(j+1) -> V buffer (j+1)&1
+                auto land_slot = [&](int j) __attribute__((always_inline)) { land_loads(j & 1, (j + 1) & 1); };
+                if (!grp_b) {
+                    for (int j = 0; j < nkt; j += 2) {
+                        cluster_m(c0, j);
                         __syncthreads();
-                        slot_loads(j + 1);
-                        cluster_v(j + 1);
-                        land_slot(j + 1);
+                        slot_loads(j);
+                        cluster_v(j);
+                        land_slot(j);
                         __syncthreads();
+                        if (j + 1 < nkt) {
+                            cluster_m(c1, j + 1);
+                            __syncthreads();
+                            slot_loads(j + 1);
+                            cluster_v(j + 1);
+                            land_slot(j + 1);
+                            __syncthreads();
+                        }
+                    }
+                } else {
+                    slot_loads(0);
+                    __syncthreads();
+                    for (int j = 0; j < nkt; j += 2) {
+                        cluster_m(c0, j);
+                        land_slot(j);
+                        __syncthreads();
+                        if (j + 1 < nkt) slot_loads(j + 1);
+                        cluster_v(j);
+                        if (j + 1 < nkt) {
+                            __syncthreads();
+                            cluster_m(c1, j + 1);
+                            land_slot(j + 1);
+                            __syncthreads();
+                            if (j + 2 < nkt) slot_loads(j + 2);
+                            cluster_v(j + 1);
+                            if (j + 2 < nkt) __syncthreads();
+                        }
                     }
                 }
             } else {
-                slot_loads(0);
-                __syncthreads();
-                for (int j = 0; j < nkt; j += 2) {
-                    cluster_m(c0, j);
-                    land_slot(j);
+                // PIPE == 2: both clusters use the MFMA pipe.
+                //     X_j : S(j+1) = K(j+1) Q^T                      (MFMA only; issues tile loads)
+                //     Y_j : O += P(j) V(j), with the softmax of S(j+1) worked in between the
+                //           MFMAs -> P(j+1)                          (MFMA + VALU)
+                //     slot   0    1    2    3   ...
+                //     A      X_0  Y_0  X_1  Y_1
+                //     B      -    X_0  Y_0  X_1
+                // Every slot then carries the MFMA work of half a tile from each wave of a SIMD
+                // and the VALU work of one softmax, instead of all MFMA work on one wave and
+                // all VALU work on the other.
+                // LDS: K(j+1) is read in slots 2j, 2j+1 and V(j) in slots 2j+1, 2j+2.  Group A
+                // moves the K tiles (K(j+2) issued at the start of X_j in slot 2j, landed when
+                // its Y_j ends in slot 2j+1), group B the V tiles (V(j+1) issued at the start of
+                // its X_j in slot 2j+1, landed when its Y_j ends in slot 2j+2): a wave in an X
+                // cluster can afford the issue stalls, it mostly waits for the shared pipe.
+                static_assert(LDP == 1, "tile loads of this order go straight to LDS");
+                constexpr int LNT = NT / 2, LLD = TILE_CHUNKS / LNT;
+                constexpr std::integral_constant<int, LNT> lnt_c{};
+                const int lt = tid & (LNT - 1), lwave = wave & (NW / 2 - 1);
+                const unsigned goff_grp = grp_b ? goff_v(lt) : goff_k(lt);
+                u32x4 none;
+                // group A: K(j+2) -> K buffer j&1;  group B: V(j+1) -> V buffer (j+1)&1
+                auto group_loads = [&](int j) __attribute__((always_inline)) {
+                    if (!grp_b) {
+                        if (j + 2 < nkt) {
+#pragma unroll
+                            for (int q = 0; q < LLD; ++q) issue_piece(lnt_c, Kh, goff_grp, lwave, j + 2, smem_b + (j & 1) * 2 * TILE_BYTES, q, none);
+                        }
+                    } else {
+                        if (j + 1 < nkt) {
+#pragma unroll
+                            for (int q = 0; q < LLD; ++q) issue_piece(lnt_c, Vh, goff_grp, lwave, j + 1, smem_b + ((j + 1) & 1) * 2 * TILE_BYTES + TILE_BYTES, q, none);
+                        }
+                    }
+                };
+                auto cluster_x = [&](auto par_c, int j) __attribute__((always_inline)) {  // par = j & 1
+                    constexpr int PAR = decltype(par_c)::value;
+                    constexpr std::integral_constant<int, PAR ^ 1> kbuf{};
+                    group_loads(j);
+                    if (tile_active(j + 1)) mfma_stream(no, yes, par_c, kbuf, pk, s);
+                };
+                auto cluster_y = [&](auto par_c, int j) __attribute__((always_inline)) {
+                    if (tile_active(j)) pv_softmax_stream(par_c, pk, s, (j + 1) * BN, tile_active(j + 1));
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this group's tile has landed
+                };
+                if (!grp_b) {
+                    for (int j = 0; j < nkt; j += 2) {
+                        cluster_x(c0, j);
+                        __syncthreads();
+                        cluster_y(c0, j);
+                        __syncthreads();
+                        if (j + 1 < nkt) {
+                            cluster_x(c1, j + 1);
+                            __syncthreads();
+                            cluster_y(c1, j + 1);
+                            __syncthreads();
+                        }
+                    }
+                } else {
                     __syncthreads();
-                    if (j + 1 < nkt) slot_loads(j + 1);
-                    cluster_v(j);
-                    if (j + 1 < nkt) {
+                    for (int j = 0; j < nkt; j += 2) {
+                        cluster_x(c0, j);
                         __syncthreads();
-                        cluster_m(c1, j + 1);
-                        land_slot(j + 1);
-                        __syncthreads();
-                        if (j + 2 < nkt) slot_loads(j + 2);
-                        cluster_v(j + 1);
-                        if (j + 2 < nkt) __syncthreads();
+                        cluster_y(c0, j);
+                        if (j + 1 < nkt) {
+                            __syncthreads();
+                            cluster_x(c1, j + 1);
+                            __syncthreads();
+                            cluster_y(c1, j + 1);
+                            if (j + 2 < nkt) __syncthreads();
+                        }
                     }
                 }
             }
         }
-    }
 
-    // ---- epilogue: normalise, round once, store O and lse
+        // ---- epilogue: normalise, round once, store O and lse.  A lane holds 8-byte pieces
+        // of one row of O; stored directly they would scatter over 32 rows per instruction.
+        // Each wave transposes its 32*QB rows through its own part of LDS instead (the K/V
+        // tiles are dead by now) and writes whole rows, 16 bytes per lane, 1 KB contiguous
+        // per instruction.  Chunk k of row r sits at chunk k ^ (r mod CPR): conflict-free
+        // row-wise reads, two-way conflicts on the column-wise writes.
+        static_assert(BM * RB <= 4 * TILE_BYTES, "the O tile must fit into the K/V buffers");
+        __syncthreads();  // every wave has finished reading the last K/V tiles
+        {
+            char* stage = smem_b + wave * (32 * QB * RB);
+            // Per-lane addresses below are the same for every work item; an opaque copy of the
+            // lane id keeps the compiler from computing them once, ahead of the item loop, and
+            // holding (or spilling) them through the tile loops.
+            int le = lane;
+            asm volatile("" : "+v"(le));
+            const int ce = le & 31, ge = le >> 5;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const float l_tot = xhalf_sum(l_run[qb]);
-        const float inv = 1.0f / l_tot;
-        const int qi = qw0 + qb * 32 + c;
-        if (qi < N) {
-            uint16_t* orow = p.out + head_off + (size_t)qi * D;
+            for (int qb = 0; qb < QB; ++qb) {
+                const float l_tot = xhalf_sum(l_run[qb]);
+                const float inv = 1.0f / l_tot;
+                const int qi = qw0 + qb * 32 + ce;
+                char* srow = stage + (qb * 32 + ce) * RB + ge * 8;
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
+                for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4) {
-                    u32x2 w;
-                    w[0] = T::pack2(o[qb][dt][4 * v4 + 0] * inv, o[qb][dt][4 * v4 + 1] * inv);
-                    w[1] = T::pack2(o[qb][dt][4 * v4 + 2] * inv, o[qb][dt][4 * v4 + 3] * inv);
-                    *reinterpret_cast<u32x2*>(orow + dt * 32 + 8 * v4 + 4 * g) = w;
-                }
-            if (g == 0) p.lse[(size_t)bh * N + qi] = m_use[qb] * p.scale + __logf(l_tot);
+                    for (int v4 = 0; v4 < 4; ++v4) {
+                        u32x2 w;
+                        w[0] = T::pack2(o[qb][dt][4 * v4 + 0] * inv, o[qb][dt][4 * v4 + 1] * inv);
+                        w[1] = T::pack2(o[qb][dt][4 * v4 + 2] * inv, o[qb][dt][4 * v4 + 3] * inv);
+                        *reinterpret_cast<u32x2*>(srow + (((dt * 4 + v4) ^ (ce & (CPR - 1))) * 16)) = w;
+                    }
+                if (ge == 0 && qi < N) p.lse[(size_t)bh * N + qi] = m_use[qb] * p.scale + __logf(l_tot);
+            }
+            asm volatile("" ::: "memory");  // same wave: LDS executes its writes and reads in order
+            uint16_t* obase = p.out + head_off + (size_t)qw0 * D;
+#pragma unroll
+            for (int i = 0; i < 32 * QB * CPR / 64; ++i) {
+                const int f = i * 64 + le, row = f / CPR, k = f % CPR;
+                const u32x4 val = *reinterpret_cast<const u32x4*>(stage + row * RB + ((k ^ (row & (CPR - 1))) * 16));
+                if (qw0 + row < N) *reinterpret_cast<u32x4*>(obase + (size_t)row * D + k * 8) = val;
+            }
         }
     }
 }
