@@ -7,7 +7,7 @@ over one batch of seeded synthetic Q/K/V that already sits in HBM.  Prints ONE J
 line.  FLOP convention: 4*B*H*N^2*d, halved for causal.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload IDX] [--variant ID]
-                  [--no-cpu-baseline] [--all]
+                  [--no-cpu-baseline] [--no-mfma-ceiling] [--all]
 """
 import argparse
 import json
@@ -25,7 +25,8 @@ MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16/fp16 MFMA peak (published)
 # `--pmc WRITE_SIZE` runs scaled by the same counters on a 256 MiB device copy (FETCH_SIZE
 # counts 2 KiB, WRITE_SIZE 1 KiB); the runs and numbers are written up under profiles/.
 MEASURED_HBM_BYTES = {
-    "cfg2": (101936 * 2.0 + 73549.6 * 1.0) * 1024,
+    "cfg2": (137699 * 2.0 + 75787.1 * 1.0) * 1024,
+    "cfg3": (334452 * 2.0 + 148992 * 1.0) * 1024,
 }
 
 
@@ -120,6 +121,8 @@ def main():
     ap.add_argument("--workload", type=int, default=2, help="index into the benchmark configs (default 2)")
     ap.add_argument("--variant", type=int, default=None, help="schedule variant id (default: library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mfma-ceiling", action="store_true",
+                    help="skip the MFMA-only kernel that measures the sustained matrix-core rate of this device")
     ap.add_argument("--all", action="store_true", help="also time the other configs (reported under 'others')")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a 256 MiB device copy (counter calibration for rocprofv3 --pmc)")
@@ -156,6 +159,15 @@ def main():
                      "frac": achieved / MFMA_PEAK_TFLOPS,
                      "traffic": MEASURED_HBM_BYTES.get(w.name) if args.variant is None else None},
     }
+    if not args.no_mfma_ceiling:
+        # what the MFMA pipe alone sustains on this device (about 0.3 s each): context for frac
+        tf_c, ghz_c = A.attn_mfma_ceiling(False)
+        tf_r, ghz_r = A.attn_mfma_ceiling(True)
+        result["roofline"]["mfma_only_kernel"] = {
+            "constant_operands": {"TFLOP/s": tf_c, "core_GHz": ghz_c},
+            "random_operands": {"TFLOP/s": tf_r, "core_GHz": ghz_r},
+            "frac_of_random_operand_rate": achieved / tf_r if tf_r > 0 else None,
+            "note": "bf16 MFMAs from registers only; with random operands the device lowers its clock"}
     if not args.no_cpu_baseline:
         base, parity = cpu_baseline(w, bits, tensors[3], tensors[4])
         result["cpu_baseline"] = base

@@ -101,6 +101,24 @@ int attn_knob_size(int knob);
 int attn_variant_coords(int variant_id, int* coords);
 int attn_variant_from_coords(const int* coords);
 
+/* How work reaches the device (host logic, no device call).  A work item is one
+ * query tile of one head (the outer, data-parallel loop of the tiled forward pass);
+ * a launch uses a grid of persistent workgroups, each of which takes items round
+ * after round from a fixed schedule: items sorted by weight (under a causal mask the
+ * last query tiles see the most keys) are dealt to the workgroups in serpentine
+ * order, inside each of the 8 XCDs over that XCD's own heads when the grid and the
+ * number of heads are multiples of 8.
+ * attn_schedule_grid returns the grid size a launch of this variant uses for the
+ * shape on a device with `compute_units` CUs (ATTN_EINVAL / ATTN_EUNSUPPORTED on bad
+ * or oversized arguments).
+ * attn_schedule_item names the item of workgroup `workgroup` (0 <= workgroup < grid)
+ * in round `round` for BH = B*H heads of nqt query tiles each: returns 1 and writes
+ * *bh (0 .. BH-1) and *qt (0 .. nqt-1), 0 when that workgroup has no item in that
+ * round (nor in any later one), ATTN_EINVAL on bad arguments.  Over all workgroups
+ * and rounds every item is named exactly once. */
+int attn_schedule_grid(int variant_id, int compute_units, int B, int H, int N);
+int attn_schedule_item(int grid, int workgroup, int BH, int nqt, int round, int* bh, int* qt);
+
 /* The variant attn_fwd uses for this shape. */
 int attn_default_variant(int N, int d, int dtype, int causal);
 
@@ -112,6 +130,19 @@ int attn_default_variant(int N, int d, int dtype, int causal);
 int attn_time_variant(const void* q, const void* k, const void* v, void* out, float* lse,
                       int B, int H, int N, int d, int causal, float scale, int dtype,
                       void* stream, int variant_id, int warmup, int iters, float* ms);
+
+/* Measurement aid for the roofline (not part of the attention path): runs a kernel
+ * that does nothing but independent 32x32x16 bf16 MFMAs from registers on every SIMD
+ * (`iters` rounds of four per wave, 8 waves per CU) and reports the rate it sustained
+ * (*tflops, host) and the core clock during the run (*core_ghz, host; 0 if the clock
+ * counters could not be read).  random_operands = 0 uses constant operands (the
+ * clock-limited peak), 1 uses operands with random signs and mantissas: the device
+ * then lowers its clock, and that rate bounds what a kernel fed real data can reach.
+ * counters: device memory, 3 x 8 bytes, written by the kernel (caller-owned).
+ * Blocks until the kernel has finished.  ATTN_EINVAL on bad arguments, ATTN_ELAUNCH
+ * if a HIP call fails. */
+int attn_mfma_ceiling(int random_operands, int iters, void* stream, unsigned long long* counters,
+                      double* tflops, double* core_ghz);
 
 /* Static text for an error code. */
 const char* attn_strerror(int code);

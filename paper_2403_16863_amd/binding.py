@@ -19,7 +19,7 @@ ATTN_OK, ATTN_EINVAL, ATTN_EUNSUPPORTED, ATTN_ELAUNCH = 0, -1, -2, -3
 SYMBOLS = ("attn_fwd", "attn_fwd_variant", "attn_num_variants", "attn_variant_supported",
            "attn_variant_desc", "attn_num_knobs", "attn_knob_name", "attn_knob_size",
            "attn_variant_coords", "attn_variant_from_coords", "attn_default_variant",
-           "attn_time_variant", "attn_strerror")
+           "attn_time_variant", "attn_strerror", "attn_schedule_grid", "attn_schedule_item", "attn_mfma_ceiling")
 
 _lib = None
 
@@ -67,6 +67,13 @@ def lib():
         L.attn_variant_from_coords.argtypes = [ctypes.POINTER(i)]
         L.attn_default_variant.restype = i
         L.attn_default_variant.argtypes = [i, i, i, i]
+        L.attn_schedule_grid.restype = i
+        L.attn_schedule_grid.argtypes = [i, i, i, i, i]
+        L.attn_schedule_item.restype = i
+        L.attn_schedule_item.argtypes = [i, i, i, i, i, ctypes.POINTER(i), ctypes.POINTER(i)]
+        L.attn_mfma_ceiling.restype = i
+        L.attn_mfma_ceiling.argtypes = [i, i, ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         L.attn_strerror.restype = ctypes.c_char_p
         L.attn_strerror.argtypes = [i]
         _lib = L
@@ -191,6 +198,36 @@ def attn_variant_from_coords(coords):
     arr = (ctypes.c_int * n)(*[int(c) for c in coords])
     rc = lib().attn_variant_from_coords(arr)
     return None if rc < 0 else rc
+
+
+def attn_schedule_grid(variant: int, compute_units: int, B: int, H: int, N: int) -> int:
+    """Grid size (persistent workgroups) a launch of this variant uses."""
+    rc = lib().attn_schedule_grid(int(variant), int(compute_units), int(B), int(H), int(N))
+    if rc < 0:
+        raise AttnError(rc, "attn_schedule_grid")
+    return rc
+
+
+def attn_schedule_item(grid: int, workgroup: int, BH: int, nqt: int, rnd: int):
+    """(bh, qt) of the item a workgroup takes in a round, or None when it has none."""
+    bh, qt = ctypes.c_int(0), ctypes.c_int(0)
+    rc = lib().attn_schedule_item(int(grid), int(workgroup), int(BH), int(nqt), int(rnd),
+                                  ctypes.byref(bh), ctypes.byref(qt))
+    if rc < 0:
+        raise AttnError(rc, "attn_schedule_item")
+    return (bh.value, qt.value) if rc == 1 else None
+
+
+def attn_mfma_ceiling(random_operands: bool, iters: int = 300000):
+    """(TFLOP/s, core clock in GHz) of a kernel of back-to-back bf16 MFMAs; see the header."""
+    import torch
+    counters = torch.zeros(3, dtype=torch.int64, device="cuda")
+    tf, ghz = ctypes.c_double(0), ctypes.c_double(0)
+    rc = lib().attn_mfma_ceiling(int(bool(random_operands)), int(iters), torch.cuda.current_stream().cuda_stream, counters.data_ptr(),
+                                 ctypes.byref(tf), ctypes.byref(ghz))
+    if rc != 0:
+        raise AttnError(rc, "attn_mfma_ceiling")
+    return tf.value, ghz.value
 
 
 def attn_default_variant(N: int, d: int, dtype: int, causal: bool) -> int:

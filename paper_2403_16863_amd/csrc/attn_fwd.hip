@@ -17,16 +17,17 @@ typedef void (*KernelFn)(const Params);
 
 struct Variant {
     int bn, nw, qb, occ, ldp, pipe, pf, prio;  // knob values
-    int coords[8];                             // lattice coordinates (indices into the knob value lists)
+    int coords[7];                             // lattice coordinates (indices into the knob value lists)
     // kernels indexed [d == 128][dtype][causal]; null = not built for that combination
     KernelFn fn[2][2][2];
 };
 
-// Knob value lists (lattice axes): bn {32,64,128}  nw {4,8}  qb {1,2}  occ {1,2}  ldp {0,1}
-// pipe {0,1,2}  pf {2,4,6,8}  prio {0,1}
-const char* const kKnobNames[] = {"bn", "nw", "qb", "occ", "ldp", "pipe", "pf", "prio"};
-const int kKnobSizes[] = {3, 2, 2, 2, 2, 3, 4, 2};
-constexpr int kNumKnobs = 8;
+// Knob value lists (lattice axes): bn {32,64,128}  nw {4,8}  qb {1,2}  ldp {0,1}
+// pipe {0,1,2}  pf {2,4,6,8}  prio {0,1}.  The occupancy target follows from nw and qb (two
+// workgroups per CU when one holds four waves of one query block each) and is no axis.
+const char* const kKnobNames[] = {"bn", "nw", "qb", "ldp", "pipe", "pf", "prio"};
+const int kKnobSizes[] = {3, 2, 2, 2, 3, 4, 2};
+constexpr int kNumKnobs = 7;
 
 #define ATTN_KN(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO) attn::Knobs<BN, NW, QB, OCC, LDP, PIPE, PF, PRIO>
 #define ATTN_KERNELS_FOR(D, ...)                                                        \
@@ -42,22 +43,21 @@ constexpr int kNumKnobs = 8;
 #define IDX_BN(x) ((x) == 32 ? 0 : (x) == 64 ? 1 : 2)
 #define IDX_NW(x) ((x) == 4 ? 0 : 1)
 #define IDX_QB(x) ((x) == 1 ? 0 : 1)
-#define IDX_OCC(x) ((x) == 1 ? 0 : 1)
 #define IDX_PF(x) ((x) / 2 - 1)
 
 #define VARIANT_BOTH(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)                                          \
     {BN, NW, QB, OCC, LDP, PIPE, PF, PRIO,                                                          \
-     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), IDX_OCC(OCC), LDP, PIPE, IDX_PF(PF), PRIO},               \
+     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), LDP, PIPE, IDX_PF(PF), PRIO},               \
      {ATTN_KERNELS_FOR(64, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO),                                   \
       ATTN_KERNELS_FOR(128, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)}}
 #define VARIANT_D64(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)                                           \
     {BN, NW, QB, OCC, LDP, PIPE, PF, PRIO,                                                          \
-     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), IDX_OCC(OCC), LDP, PIPE, IDX_PF(PF), PRIO},               \
+     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), LDP, PIPE, IDX_PF(PF), PRIO},               \
      {ATTN_KERNELS_FOR(64, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO), ATTN_NO_KERNELS}}
 
 #define VARIANT_D128(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)                                          \
     {BN, NW, QB, OCC, LDP, PIPE, PF, PRIO,                                                          \
-     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), IDX_OCC(OCC), LDP, PIPE, IDX_PF(PF), PRIO},               \
+     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), LDP, PIPE, IDX_PF(PF), PRIO},               \
      {ATTN_NO_KERNELS, ATTN_KERNELS_FOR(128, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)}}
 
 const Variant kVariants[] = {
@@ -92,6 +92,17 @@ int cu_count() {
         cached[dev] = n;
     }
     return cached[dev];
+}
+
+// Persistent workgroups: as many as the device keeps resident (occ per CU), a multiple of 8
+// when every XCD can be given whole heads, never more than there are work items.
+long long grid_size(int cus, int occ, int BH, long long nqt) {
+    const long long total = (long long)BH * nqt, resident = (long long)cus * occ;
+    if ((BH & 7) == 0 && (resident & 7) == 0) {
+        const long long per_xcd_items = (long long)(BH >> 3) * nqt, per_xcd_wg = resident >> 3;
+        return 8 * (per_xcd_items < per_xcd_wg ? per_xcd_items : per_xcd_wg);
+    }
+    return total < resident ? total : resident;
 }
 
 bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
@@ -146,22 +157,13 @@ int launch(const void* q, const void* k, const void* v, void* out, float* lse, i
     p.N = N;
     p.nqt = (int)nqt;
     p.BH = B * H;
-    p.total_wg = (int)total;
     // The kernel tracks the running maximum of the raw dot products, which needs a
     // positive multiplier: a negative scale is moved into the sign of Q, a zero scale
     // into Q = 0.
     p.qmode = scale > 0.f ? 0 : (scale < 0.f ? 1 : 2);
     p.scale = scale > 0.f ? scale : (scale < 0.f ? -scale : 1.0f);
     p.scale_l2 = p.scale * 1.44269504088896340736f;
-    // Persistent workgroups: as many as the device keeps resident (occ per CU), a multiple
-    // of 8 when every XCD can be given whole heads, never more than there are work items.
-    p.order = 2;
-    const long long resident = (long long)cu_count() * var.occ;
-    long long grid = total < resident ? total : resident;
-    if ((p.BH & 7) == 0 && (resident & 7) == 0) {
-        const long long per_xcd_items = (long long)(p.BH >> 3) * nqt, per_xcd_wg = resident >> 3;
-        grid = 8 * (per_xcd_items < per_xcd_wg ? per_xcd_items : per_xcd_wg);
-    }
+    const long long grid = grid_size(cu_count(), var.occ, p.BH, nqt);
     // The launch's own return code is used (not hipGetLastError, which can report a
     // stale, unrelated status left behind by another library's earlier call).
     void* args[] = {&p};
@@ -171,11 +173,76 @@ int launch(const void* q, const void* k, const void* v, void* out, float* lse, i
     return e == hipSuccess ? ATTN_OK : ATTN_ELAUNCH;
 }
 
+
+// ---- measurement aid: what the MFMA pipe sustains on this device.  Every wave issues
+// independent 32x32x16 bf16 MFMAs back to back (four accumulators, operands fixed in
+// registers, no memory traffic), two waves per SIMD.  With constant operands this reaches
+// the clock-limited peak; with random operands the switching activity makes the device
+// lower its clock (power management), which bounds what any kernel fed real data can reach.
+__global__ __launch_bounds__(256) void mfma_ceiling_kernel(unsigned long long* counters, int iters, int random_operands) {
+    typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+    typedef float f32x16 __attribute__((ext_vector_type(16)));
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 a[4], b[4];
+    unsigned st = (blockIdx.x * 256 + threadIdx.x) * 2654435761u + 12345u;
+    for (int n = 0; n < 4; ++n)
+        for (int j = 0; j < 4; ++j) {
+            st = st * 1664525u + 1013904223u;
+            unsigned ra = st;
+            st = st * 1664525u + 1013904223u;
+            unsigned rb = st;
+            if (!random_operands) {
+                ra = rb = 0x3f803f80u;  // 1.0, 1.0
+            } else {  // random sign and mantissa, exponent 126 or 127: magnitudes in [0.5, 2)
+                ra = (ra & 0x807f807fu) | 0x3f003f00u | ((ra >> 3) & 0x00800080u);
+                rb = (rb & 0x807f807fu) | 0x3f003f00u | ((rb >> 5) & 0x00800080u);
+            }
+            a[n][j] = ra;
+            b[n][j] = rb;
+        }
+    f32x16 acc[4];
+    for (int n = 0; n < 4; ++n)
+        for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
+    const unsigned long long c0 = clock64(), r0 = wall_clock64();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int n = 0; n < 4; ++n)
+            acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[n]), __builtin_bit_cast(bf16x8, b[n]), acc[n], 0, 0, 0);
+    }
+    const unsigned long long c1 = clock64(), r1 = wall_clock64();
+    float sum = 0;
+    for (int n = 0; n < 4; ++n)
+        for (int v = 0; v < 16; ++v) sum += acc[n][v];
+    if (blockIdx.x == 7 && threadIdx.x == 0) {
+        counters[0] = c1 - c0;  // core clock cycles
+        counters[1] = r1 - r0;  // ticks of the constant 100 MHz clock
+    }
+    if (sum == 1.2345e-30f) counters[2] = 1;  // keeps the accumulators alive
+}
+
 }  // namespace
 
 extern "C" {
 
 int attn_num_variants(void) { return kNumVariants; }
+
+int attn_schedule_grid(int variant_id, int compute_units, int B, int H, int N) {
+    if (variant_id < 0 || variant_id >= kNumVariants || compute_units < 1 || B < 1 || H < 1 || N < 1) return ATTN_EINVAL;
+    const Variant& var = kVariants[variant_id];
+    const int bm = 32 * var.qb * var.nw;
+    const long long nqt = ((long long)N + bm - 1) / bm, g = grid_size(compute_units, var.occ, B * H, nqt);
+    if ((long long)B * H > 0x7fffffffLL / nqt || g > 0x7fffffffLL) return ATTN_EUNSUPPORTED;
+    return (int)g;
+}
+
+int attn_schedule_item(int grid, int workgroup, int BH, int nqt, int round, int* bh, int* qt) {
+    if (grid < 1 || workgroup < 0 || workgroup >= grid || BH < 1 || nqt < 1 || round < 0 || !bh || !qt) return ATTN_EINVAL;
+    int b = 0, q = 0;
+    if (!attn::schedule_item(grid, workgroup, BH, nqt, round, b, q)) return 0;
+    *bh = b;
+    *qt = q;
+    return 1;
+}
 
 int attn_variant_supported(int variant_id, int d, int dtype, int causal) {
     if (variant_id < 0 || variant_id >= kNumVariants) return ATTN_EINVAL;
@@ -209,15 +276,18 @@ int attn_variant_from_coords(const int* coords) {
     return ATTN_EINVAL;
 }
 
-// Defaults chosen from the measured sweep over the variant table on MI355X: the
-// two-cluster ping-pong order wins for head_dim 128, the free-running order with raised
-// MFMA-stream priority for head_dim 64.  (Ids index kVariants.)
+// Defaults chosen from the measured search over the variant table on MI355X: the
+// two-cluster ping-pong order (256-row query tiles) wins for head_dim 128 and for long
+// sequences with head_dim 64; short sequences with head_dim 64 have too few such tiles to
+// go round and run the free-running order on 128-row tiles.  (Ids index kVariants.)
 constexpr int kDefaultD128 = 11;
-constexpr int kDefaultD64 = 3;
+constexpr int kDefaultD64Long = 10;
+constexpr int kDefaultD64Short = 3;
 
 int attn_default_variant(int N, int d, int dtype, int causal) {
-    (void)N; (void)dtype; (void)causal;
-    return d == 128 ? kDefaultD128 : kDefaultD64;
+    (void)dtype; (void)causal;
+    if (d == 128) return kDefaultD128;
+    return N >= 2048 ? kDefaultD64Long : kDefaultD64Short;
 }
 
 int attn_fwd_variant(const void* q, const void* k, const void* v, void* out, float* lse, int B, int H,
@@ -255,6 +325,32 @@ int attn_time_variant(const void* q, const void* k, const void* v, void* out, fl
     hipEventDestroy(e0);
     hipEventDestroy(e1);
     return rc;
+}
+
+int attn_mfma_ceiling(int random_operands, int iters, void* stream, unsigned long long* counters,
+                      double* tflops, double* core_ghz) {
+    if (iters < 1 || !counters || !tflops || !core_ghz) return ATTN_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const int blocks = 2 * cu_count();  // 8 waves per CU
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return ATTN_ELAUNCH;
+    if (hipEventCreate(&e1) != hipSuccess) { hipEventDestroy(e0); return ATTN_ELAUNCH; }
+    int rc = ATTN_OK;
+    float ms = 0.f;
+    unsigned long long h[2] = {0, 0};
+    void* args[] = {&counters, &iters, &random_operands};
+    if (hipEventRecord(e0, s) != hipSuccess ||
+        hipLaunchKernel((const void*)mfma_ceiling_kernel, dim3(blocks), dim3(256), args, 0, s) != hipSuccess ||
+        hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+        hipEventElapsedTime(&ms, e0, e1) != hipSuccess ||
+        hipMemcpy(h, counters, sizeof h, hipMemcpyDeviceToHost) != hipSuccess)
+        rc = ATTN_ELAUNCH;
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    if (rc != ATTN_OK) return rc;
+    *tflops = (double)blocks * 4 * (double)iters * 4 * 32768.0 / ((double)ms * 1e-3) / 1e12;
+    *core_ghz = h[1] ? (double)h[0] / ((double)h[1] * 10.0) : 0.0;
+    return ATTN_OK;
 }
 
 const char* attn_strerror(int code) {

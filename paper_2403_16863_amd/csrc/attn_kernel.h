@@ -53,14 +53,8 @@ struct Params {
     int H, N;
     int nqt;          // query tiles per head
     int BH;           // B * H
-    int total_wg;     // nqt * B * H = number of work items (one query tile of one head each)
     float scale;      // multiplies q'.k, always > 0 (see qmode)
     float scale_l2;   // scale * log2(e)
-    int order;        // how work items reach workgroups:
-                      // 0, 1: one item per workgroup (grid = total_wg), each XCD a contiguous run of
-                      //       ids, inside a head (0) or across the XCD's heads (1) heaviest tile first;
-                      // 2: persistent workgroups (grid = resident workgroups), each takes the items
-                      //    of a fixed serpentine schedule one after the other
     int qmode;        // 0: q' = q;  1: q' = -q (caller's scale was negative);
                       // 2: q' = 0 (caller's scale was zero, kernel runs with scale 1)
 };
@@ -146,6 +140,33 @@ __device__ __forceinline__ int v_swz_slot(int row, int slot) {
     return slot ^ (D == 128 ? code : (code & 3));
 }
 
+// ---- work items and their schedule.  A work item is one query tile of one head; the grid
+// holds G persistent workgroups (as many as the device keeps resident), and workgroup gidx
+// takes, in round 0, 1, 2 ..., the item this function names, until it returns false.
+// Items in head-major order, inside a head from the last query tile (the heaviest under a
+// causal mask) to the first, are dealt to the workgroups in serpentine order (0..G-1,
+// G-1..0, ...): a workgroup's items of two consecutive rounds then sit at mirrored
+// positions of the weight sawtooth, so the sums come out even, and at any time the
+// workgroups of a round work on few heads, whose K and V stay in L2.  Workgroups are placed
+// round-robin on the 8 XCDs, each with its own L2: when G and the number of heads BH are
+// multiples of 8, the deal runs inside each XCD over that XCD's heads (x, x+8, ...), so all
+// query tiles of a head share one L2.  Every item is named exactly once over all (gidx, round).
+__host__ __device__ inline bool schedule_item(int G, int gidx, int BH, int nqt, int round, int& bh, int& qt) {
+    int r, nh, h0, hs;
+    if ((G & 7) == 0 && (BH & 7) == 0) {
+        const int C = G >> 3, cidx = gidx >> 3;
+        r = round * C + ((round & 1) ? C - 1 - cidx : cidx);
+        nh = BH >> 3, h0 = gidx & 7, hs = 8;
+    } else {
+        r = round * G + ((round & 1) ? G - 1 - gidx : gidx);
+        nh = BH, h0 = 0, hs = 1;
+    }
+    if (r >= nh * nqt) return false;
+    qt = nqt - 1 - r % nqt;
+    bh = h0 + hs * (r / nqt);
+    return true;
+}
+
 // Schedule / shape knobs of one variant (the lattice the search walks).
 template <int BN_, int NW_, int QB_, int OCC_, int LDP_, int PIPE_, int PF_, int PRIO_>
 struct Knobs {
@@ -187,51 +208,8 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
     const int g = lane >> 5;
     const int c = lane & 31;
 
-    // ---- work item (head, query tile) of this workgroup in a given round.
-    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: all query tiles
-    // of a head should run on one XCD, and the heaviest (last, under a causal mask) query
-    // tiles should start first.
     auto item_of_round = [&](int round, int& bh, int& qt) __attribute__((always_inline)) -> bool {
-        if (p.order == 2) {
-            // Persistent: items sorted by weight (query tile descending, then head) are dealt
-            // to the G workgroups in serpentine order (0..G-1, G-1..0, ...), so the sums of
-            // linearly decreasing weights come out even.  With whole heads per XCD the deal
-            // runs inside each XCD over that XCD's heads (x, x+8, ...).
-            const int G = (int)gridDim.x, gidx = (int)blockIdx.x;
-            int r, nh, h0, hs;
-            if ((G & 7) == 0 && (p.BH & 7) == 0) {
-                const int C = G >> 3, cidx = gidx >> 3;
-                r = round * C + ((round & 1) ? C - 1 - cidx : cidx);
-                nh = p.BH >> 3, h0 = gidx & 7, hs = 8;
-            } else {
-                r = round * G + ((round & 1) ? G - 1 - gidx : gidx);
-                nh = p.BH, h0 = 0, hs = 1;
-            }
-            if (r >= nh * p.nqt) return false;
-            qt = p.nqt - 1 - r / nh;
-            bh = h0 + hs * (r % nh);
-            return true;
-        }
-        if (round > 0) return false;
-        // One item per workgroup: give each XCD a contiguous run of logical ids.
-        const int bid = blockIdx.x, xcd = bid & 7, slot = bid >> 3;
-        const int base = p.total_wg >> 3, rem = p.total_wg & 7;
-        const int first = xcd < rem ? xcd * (base + 1) : rem * (base + 1) + (xcd - rem) * base;
-        const int count = base + (xcd < rem ? 1 : 0);
-        const int logical = first + slot;
-        const int h_lo = first / p.nqt, h_hi = (first + count - 1) / p.nqt;  // heads this XCD touches
-        const int nh = h_hi - h_lo + 1;
-        if (p.order == 1 && first % p.nqt == 0 && count % p.nqt == 0) {
-            // the XCD's heads side by side, heaviest query tiles first (the last workgroups
-            // to start are then the lightest ones, whatever the head)
-            const int r = logical - first;  // 0 .. count-1, count = nh * nqt
-            bh = h_lo + r % nh;
-            qt = p.nqt - 1 - r / nh;
-        } else {
-            bh = logical / p.nqt;
-            qt = p.nqt - 1 - (logical - bh * p.nqt);
-        }
-        return true;
+        return schedule_item((int)gridDim.x, (int)blockIdx.x, p.BH, p.nqt, round, bh, qt);
     };
     const int N = p.N;
     for (int round = 0;; ++round) {
