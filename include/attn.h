@@ -131,6 +131,27 @@ int attn_time_variant(const void* q, const void* k, const void* v, void* out, fl
                       int B, int H, int N, int d, int causal, float scale, int dtype,
                       void* stream, int variant_id, int warmup, int iters, float* ms);
 
+/* Instruction-level schedule search (Sec. 3.1 to 3.3 applied to machine code): the
+ * assembly of a variant's kernel, with the positions of some memory instructions changed,
+ * is assembled into a code object outside this library and run through these calls.
+ * attn_codeobj_load loads the code object file `path` (host string) and looks up
+ * `kernel_name` in it; the kernel must be a re-scheduled copy of the kernel that
+ * `variant_id` uses for (d, dtype, causal): same arguments, same block size, same LDS.
+ * Returns a handle >= 0, or ATTN_EINVAL (bad argument), ATTN_EUNSUPPORTED (no such
+ * variant kernel, or all 64 handles in use), ATTN_ELAUNCH (file or symbol not loadable).
+ * attn_fwd_codeobj / attn_time_codeobj behave like attn_fwd_variant / attn_time_variant
+ * with the loaded kernel in place of the variant's own; a shape that does not match what
+ * the handle was loaded for gives ATTN_EUNSUPPORTED.  attn_codeobj_unload releases a
+ * handle; the caller makes sure no launch of it is still in flight.  The handle table is
+ * process-wide and not synchronised: use it from one thread. */
+int attn_codeobj_load(const char* path, const char* kernel_name, int variant_id, int d, int dtype, int causal);
+int attn_codeobj_unload(int handle);
+int attn_fwd_codeobj(int handle, const void* q, const void* k, const void* v, void* out, float* lse,
+                     int B, int H, int N, int d, int causal, float scale, int dtype, void* stream);
+int attn_time_codeobj(int handle, const void* q, const void* k, const void* v, void* out, float* lse,
+                      int B, int H, int N, int d, int causal, float scale, int dtype, void* stream,
+                      int warmup, int iters, float* ms);
+
 /* Measurement aid for the roofline (not part of the attention path): runs a kernel
  * that does nothing but independent 32x32x16 bf16 MFMAs from registers on every SIMD
  * (`iters` rounds of four per wave, 8 waves per CU) and reports the rate it sustained

@@ -19,7 +19,8 @@ ATTN_OK, ATTN_EINVAL, ATTN_EUNSUPPORTED, ATTN_ELAUNCH = 0, -1, -2, -3
 SYMBOLS = ("attn_fwd", "attn_fwd_variant", "attn_num_variants", "attn_variant_supported",
            "attn_variant_desc", "attn_num_knobs", "attn_knob_name", "attn_knob_size",
            "attn_variant_coords", "attn_variant_from_coords", "attn_default_variant",
-           "attn_time_variant", "attn_strerror", "attn_schedule_grid", "attn_schedule_item", "attn_mfma_ceiling")
+           "attn_time_variant", "attn_strerror", "attn_schedule_grid", "attn_schedule_item", "attn_mfma_ceiling",
+           "attn_codeobj_load", "attn_codeobj_unload", "attn_fwd_codeobj", "attn_time_codeobj")
 
 _lib = None
 
@@ -71,6 +72,14 @@ def lib():
         L.attn_schedule_grid.argtypes = [i, i, i, i, i]
         L.attn_schedule_item.restype = i
         L.attn_schedule_item.argtypes = [i, i, i, i, i, ctypes.POINTER(i), ctypes.POINTER(i)]
+        L.attn_codeobj_load.restype = i
+        L.attn_codeobj_load.argtypes = [ctypes.c_char_p, ctypes.c_char_p, i, i, i, i]
+        L.attn_codeobj_unload.restype = i
+        L.attn_codeobj_unload.argtypes = [i]
+        L.attn_fwd_codeobj.restype = i
+        L.attn_fwd_codeobj.argtypes = [i] + common
+        L.attn_time_codeobj.restype = i
+        L.attn_time_codeobj.argtypes = [i] + common + [i, i, ctypes.POINTER(ctypes.c_float)]
         L.attn_mfma_ceiling.restype = i
         L.attn_mfma_ceiling.argtypes = [i, i, ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -141,6 +150,41 @@ def attn_time_variant(q, k, v, out, lse, causal: bool, scale: float, variant_id:
                                  int(variant_id), int(warmup), int(iters), ms)
     if rc != ATTN_OK:
         raise AttnError(rc, f"attn_time_variant({variant_id})")
+    return list(ms)
+
+
+def attn_codeobj_load(path: str, kernel_name: str, variant_id: int, d: int, dtype: int, causal: bool) -> int:
+    """Handle of a kernel loaded from a code object file (a re-scheduled copy of the kernel
+    variant_id uses for this d, dtype, causal)."""
+    rc = lib().attn_codeobj_load(os.fsencode(path), kernel_name.encode(), int(variant_id), int(d),
+                                 int(dtype), int(bool(causal)))
+    if rc < 0:
+        raise AttnError(rc, f"attn_codeobj_load({path})")
+    return rc
+
+
+def attn_codeobj_unload(handle: int) -> None:
+    rc = lib().attn_codeobj_unload(int(handle))
+    if rc != ATTN_OK:
+        raise AttnError(rc, "attn_codeobj_unload")
+
+
+def attn_fwd_codeobj(handle: int, q, k, v, out, lse, causal: bool, scale: float, stream=None) -> None:
+    (ptrs_shape), dt, st = _marshal(q, k, v, out, lse, stream)
+    rc = lib().attn_fwd_codeobj(int(handle), *ptrs_shape, int(bool(causal)), float(scale), dt, st)
+    if rc != ATTN_OK:
+        raise AttnError(rc, f"attn_fwd_codeobj({handle})")
+
+
+def attn_time_codeobj(handle: int, q, k, v, out, lse, causal: bool, scale: float,
+                      warmup: int = 10, iters: int = 50, stream=None):
+    """Per-launch elapsed milliseconds of a loaded kernel, HIP-event timed."""
+    (ptrs_shape), dt, st = _marshal(q, k, v, out, lse, stream)
+    ms = (ctypes.c_float * int(iters))()
+    rc = lib().attn_time_codeobj(int(handle), *ptrs_shape, int(bool(causal)), float(scale), dt, st,
+                                 int(warmup), int(iters), ms)
+    if rc != ATTN_OK:
+        raise AttnError(rc, f"attn_time_codeobj({handle})")
     return list(ms)
 
 

@@ -135,8 +135,12 @@ int check_args(const void* q, const void* k, const void* v, void* out, float* ls
     return ATTN_OK;
 }
 
+// Launches the variant's own kernel, or, when `module_fn` is given, a kernel loaded from a
+// code object that was derived from that variant's kernel (same arguments, same grid, same
+// block, same LDS).
 int launch(const void* q, const void* k, const void* v, void* out, float* lse, int B, int H, int N,
-           int d, int causal, float scale, int dtype, void* stream, int variant_id) {
+           int d, int causal, float scale, int dtype, void* stream, int variant_id,
+           hipFunction_t module_fn = nullptr) {
     const int rc = check_args(q, k, v, out, lse, B, H, N, d, scale, dtype, variant_id);
     if (rc != ATTN_OK) return rc;
     const Variant& var = kVariants[variant_id];
@@ -167,10 +171,57 @@ int launch(const void* q, const void* k, const void* v, void* out, float* lse, i
     // The launch's own return code is used (not hipGetLastError, which can report a
     // stale, unrelated status left behind by another library's earlier call).
     void* args[] = {&p};
-    const hipError_t e = hipLaunchKernel((const void*)fn, dim3((unsigned)grid), dim3(var.nw * 64),
-                                         args, 0, (hipStream_t)stream);
-    if (e != hipSuccess) fprintf(stderr, "attn: hipLaunchKernel failed: %s (%d), grid=%lld block=%d\n", hipGetErrorString(e), (int)e, grid, var.nw * 64);
+    const hipError_t e =
+        module_fn ? hipModuleLaunchKernel(module_fn, (unsigned)grid, 1, 1, var.nw * 64, 1, 1, 0, (hipStream_t)stream, args, nullptr)
+                  : hipLaunchKernel((const void*)fn, dim3((unsigned)grid), dim3(var.nw * 64), args, 0, (hipStream_t)stream);
+    if (e != hipSuccess) fprintf(stderr, "attn: kernel launch failed: %s (%d), grid=%lld block=%d\n", hipGetErrorString(e), (int)e, grid, var.nw * 64);
     return e == hipSuccess ? ATTN_OK : ATTN_ELAUNCH;
+}
+
+// ---- kernels loaded from code objects (instruction-level schedule search).  A small fixed
+// table; a slot records what the kernel was derived from so that a launch can be refused
+// when the shape does not match.
+struct LoadedKernel {
+    hipModule_t module = nullptr;
+    hipFunction_t fn = nullptr;
+    int variant_id = -1, d = 0, dtype = 0, causal = 0;
+};
+constexpr int kMaxLoaded = 64;
+LoadedKernel g_loaded[kMaxLoaded];
+
+const LoadedKernel* loaded_for(int handle, int d, int dtype, int causal, int* rc) {
+    if (handle < 0 || handle >= kMaxLoaded || !g_loaded[handle].fn) { *rc = ATTN_EINVAL; return nullptr; }
+    const LoadedKernel& lk = g_loaded[handle];
+    if (lk.d != d || lk.dtype != dtype || lk.causal != (causal ? 1 : 0)) { *rc = ATTN_EUNSUPPORTED; return nullptr; }
+    *rc = ATTN_OK;
+    return &lk;
+}
+
+// Shared by the two timing entry points: `warmup` untimed launches, then `iters` launches
+// each bracketed by its own pair of events.
+template <class LaunchFn>
+int time_launches(LaunchFn&& do_launch, void* stream, int warmup, int iters, float* ms) {
+    if (!ms || iters < 1 || warmup < 0) return ATTN_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    for (int i = 0; i < warmup; ++i) {
+        const int rc = do_launch();
+        if (rc != ATTN_OK) return rc;
+    }
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return ATTN_ELAUNCH;
+    if (hipEventCreate(&e1) != hipSuccess) { hipEventDestroy(e0); return ATTN_ELAUNCH; }
+    int rc = ATTN_OK;
+    for (int i = 0; i < iters && rc == ATTN_OK; ++i) {
+        if (hipEventRecord(e0, s) != hipSuccess) { rc = ATTN_ELAUNCH; break; }
+        rc = do_launch();
+        if (rc != ATTN_OK) break;
+        if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+            hipEventElapsedTime(&ms[i], e0, e1) != hipSuccess)
+            rc = ATTN_ELAUNCH;
+    }
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    return rc;
 }
 
 
@@ -304,27 +355,64 @@ int attn_fwd(const void* q, const void* k, const void* v, void* out, float* lse,
 int attn_time_variant(const void* q, const void* k, const void* v, void* out, float* lse, int B, int H,
                       int N, int d, int causal, float scale, int dtype, void* stream, int variant_id,
                       int warmup, int iters, float* ms) {
-    if (!ms || iters < 1 || warmup < 0) return ATTN_EINVAL;
-    hipStream_t s = (hipStream_t)stream;
-    for (int i = 0; i < warmup; ++i) {
-        const int rc = launch(q, k, v, out, lse, B, H, N, d, causal, scale, dtype, stream, variant_id);
-        if (rc != ATTN_OK) return rc;
+    return time_launches([&] { return launch(q, k, v, out, lse, B, H, N, d, causal, scale, dtype, stream, variant_id); },
+                         stream, warmup, iters, ms);
+}
+
+int attn_codeobj_load(const char* path, const char* kernel_name, int variant_id, int d, int dtype, int causal) {
+    if (!path || !kernel_name || variant_id < 0 || variant_id >= kNumVariants) return ATTN_EINVAL;
+    if ((d != 64 && d != 128) || (dtype != ATTN_F16 && dtype != ATTN_BF16)) return ATTN_EINVAL;
+    if (!kVariants[variant_id].fn[d == 128][dtype][causal ? 1 : 0]) return ATTN_EUNSUPPORTED;
+    int slot = -1;
+    for (int i = 0; i < kMaxLoaded; ++i)
+        if (!g_loaded[i].fn) { slot = i; break; }
+    if (slot < 0) return ATTN_EUNSUPPORTED;  // table full: unload something first
+    // A failed runtime call leaves its status behind for whoever asks next (another library in
+    // the process would report it as its own): look at the file first, and consume the status
+    // of a load that fails anyway.
+    if (FILE* f = fopen(path, "rb")) fclose(f);
+    else return ATTN_ELAUNCH;
+    LoadedKernel lk;
+    if (hipModuleLoad(&lk.module, path) != hipSuccess) {
+        (void)hipGetLastError();
+        return ATTN_ELAUNCH;
     }
-    hipEvent_t e0, e1;
-    if (hipEventCreate(&e0) != hipSuccess) return ATTN_ELAUNCH;
-    if (hipEventCreate(&e1) != hipSuccess) { hipEventDestroy(e0); return ATTN_ELAUNCH; }
-    int rc = ATTN_OK;
-    for (int i = 0; i < iters && rc == ATTN_OK; ++i) {
-        if (hipEventRecord(e0, s) != hipSuccess) { rc = ATTN_ELAUNCH; break; }
-        rc = launch(q, k, v, out, lse, B, H, N, d, causal, scale, dtype, stream, variant_id);
-        if (rc != ATTN_OK) break;
-        if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
-            hipEventElapsedTime(&ms[i], e0, e1) != hipSuccess)
-            rc = ATTN_ELAUNCH;
+    if (hipModuleGetFunction(&lk.fn, lk.module, kernel_name) != hipSuccess) {
+        (void)hipGetLastError();
+        hipModuleUnload(lk.module);
+        return ATTN_ELAUNCH;
     }
-    hipEventDestroy(e0);
-    hipEventDestroy(e1);
-    return rc;
+    lk.variant_id = variant_id;
+    lk.d = d;
+    lk.dtype = dtype;
+    lk.causal = causal ? 1 : 0;
+    g_loaded[slot] = lk;
+    return slot;
+}
+
+int attn_codeobj_unload(int handle) {
+    if (handle < 0 || handle >= kMaxLoaded || !g_loaded[handle].fn) return ATTN_EINVAL;
+    const hipError_t e = hipModuleUnload(g_loaded[handle].module);
+    g_loaded[handle] = LoadedKernel();
+    return e == hipSuccess ? ATTN_OK : ATTN_ELAUNCH;
+}
+
+int attn_fwd_codeobj(int handle, const void* q, const void* k, const void* v, void* out, float* lse,
+                     int B, int H, int N, int d, int causal, float scale, int dtype, void* stream) {
+    int rc;
+    const LoadedKernel* lk = loaded_for(handle, d, dtype, causal, &rc);
+    if (!lk) return rc;
+    return launch(q, k, v, out, lse, B, H, N, d, causal, scale, dtype, stream, lk->variant_id, lk->fn);
+}
+
+int attn_time_codeobj(int handle, const void* q, const void* k, const void* v, void* out, float* lse,
+                      int B, int H, int N, int d, int causal, float scale, int dtype, void* stream,
+                      int warmup, int iters, float* ms) {
+    int rc;
+    const LoadedKernel* lk = loaded_for(handle, d, dtype, causal, &rc);
+    if (!lk) return rc;
+    return time_launches([&] { return launch(q, k, v, out, lse, B, H, N, d, causal, scale, dtype, stream, lk->variant_id, lk->fn); },
+                         stream, warmup, iters, ms);
 }
 
 int attn_mfma_ceiling(int random_operands, int iters, void* stream, unsigned long long* counters,

@@ -300,20 +300,17 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
         const unsigned goffK0 = goff_k(tid), goffV0 = goff_v(tid);
         u32x4 kst[LDP == 0 ? LD_PER_THREAD : 1], vst[LDP == 0 ? LD_PER_THREAD : 1];
 
-        // Piece i of tile j: the source is a wave-uniform base (tile start + i * LNT / CPR rows)
-        // plus the per-lane 32-bit offset.  The tile index is clamped to the last tile (a
-        // redundant reload into a buffer nobody reads any more is cheaper than a branch in
-        // every iteration).  Only the last, ragged tile takes the slow path, where rows past
-        // the end of the sequence are redirected to the last row (their scores are masked, so
-        // only finiteness of what is loaded matters).
-        auto issue_piece = [&](auto lnt_c, const char* head, unsigned goff0, int lwave, int j, char* lds_tile, int i,
-                               u32x4& stage) __attribute__((always_inline)) {
+        // Piece i of the tile that starts at key row kt0: the source is a wave-uniform base
+        // (tile start + i * LNT / CPR rows) plus the per-lane 32-bit offset.  `whole` says that
+        // the tile lies inside the sequence; otherwise rows past the end are redirected to the
+        // last row (their scores are masked, so only finiteness of what is loaded matters).
+        auto issue_piece = [&](auto lnt_c, bool whole, const char* head, unsigned goff0, int lwave, int kt0, char* lds_tile,
+                               int i, u32x4& stage) __attribute__((always_inline)) {
             constexpr int LNT = decltype(lnt_c)::value;
             static_assert(LNT % 256 == 0 && TILE_CHUNKS % LNT == 0, "load mapping assumes whole swizzle periods per piece");
             constexpr int ROWS_PER_PIECE = LNT / CPR;
-            const int kt0 = min(j, nkt - 1) * BN;
             char* dst = lds_tile + (i * LNT + lwave * 64) * 16;
-            if (kt0 + BN <= N) {
+            if (whole) {
                 const char* pb = head + (size_t)kt0 * RB + (size_t)(i * ROWS_PER_PIECE * RB);
                 if constexpr (LDP == 1)
                     load_to_lds_16(pb, goff0, lds_address(dst));
@@ -328,13 +325,33 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
                     stage = *reinterpret_cast<const u32x4*>(src);
             }
         };
-        auto issue_tile = [&](const char* head, unsigned goff0, int j, char* lds_tile, u32x4(&stage)[LDP == 0 ? LD_PER_THREAD : 1]) __attribute__((always_inline)) {
+        // K tile jk into K buffer kbuf and / or V tile jv into V buffer vbuf (a negative index
+        // skips that tile).  Tile indices are clamped to the last tile (a redundant reload into
+        // a buffer nobody reads any more is cheaper than a branch in every iteration).  One
+        // decision covers all pieces: the common case is straight-line code, a few scalar
+        // operations and the loads, which also leaves their placement open to scheduling.
+        auto issue_tiles = [&](int jk, int kbuf, int jv, int vbuf) __attribute__((always_inline)) {
+            constexpr std::integral_constant<int, NT> nt_c{};
+            const int ktk = min(jk, nkt - 1) * BN, ktv = min(jv, nkt - 1) * BN;
+            const bool whole = max(ktk, ktv) + BN <= N;
+            auto pieces = [&](auto whole_c) __attribute__((always_inline)) {
+                constexpr bool W = decltype(whole_c)::value;
+                if (jk >= 0) {
 #pragma unroll
-            for (int i = 0; i < LD_PER_THREAD; ++i)
-                issue_piece(std::integral_constant<int, NT>{}, head, goff0, wave, j, lds_tile, i, stage[LDP == 0 ? i : 0]);
+                    for (int i = 0; i < LD_PER_THREAD; ++i)
+                        issue_piece(nt_c, W, Kh, goffK0, wave, ktk, smem_b + kbuf * 2 * TILE_BYTES, i, kst[LDP == 0 ? i : 0]);
+                }
+                if (jv >= 0) {
+#pragma unroll
+                    for (int i = 0; i < LD_PER_THREAD; ++i)
+                        issue_piece(nt_c, W, Vh, goffV0, wave, ktv, smem_b + vbuf * 2 * TILE_BYTES + TILE_BYTES, i, vst[LDP == 0 ? i : 0]);
+                }
+            };
+            if (whole) pieces(std::true_type{});
+            else pieces(std::false_type{});
         };
-        auto issue_k = [&](int j, int buf) __attribute__((always_inline)) { issue_tile(Kh, goffK0, j, smem_b + buf * 2 * TILE_BYTES, kst); };
-        auto issue_v = [&](int j, int buf) __attribute__((always_inline)) { issue_tile(Vh, goffV0, j, smem_b + buf * 2 * TILE_BYTES + TILE_BYTES, vst); };
+        auto issue_k = [&](int j, int buf) __attribute__((always_inline)) { issue_tiles(j, buf, -1, 0); };
+        auto issue_v = [&](int j, int buf) __attribute__((always_inline)) { issue_tiles(-1, 0, j, buf); };
         // make the tiles issued last visible in LDS to this thread (K into buffer kbuf, V into vbuf)
         auto land_loads = [&](int kbuf, int vbuf) __attribute__((always_inline)) {
             if constexpr (LDP == 1) {
@@ -596,8 +613,7 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
             // Overlap of MFMA and VALU work comes from the other waves resident on the SIMD.
             auto step = [&](auto buf_c, int j) __attribute__((always_inline)) {
                 constexpr int BUF = decltype(buf_c)::value;
-                issue_k(j + 1, BUF ^ 1);
-                issue_v(j + 1, BUF ^ 1);
+                issue_tiles(j + 1, BUF ^ 1, j + 1, BUF ^ 1);
                 if (tile_active(j)) {
                     mfma_stream(no, yes, buf_c, buf_c, pk, s);
                     softmax_tile(s, pk, j * BN);
@@ -666,8 +682,7 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
                 // Every wave issues its share of a tile at the start of one of its V clusters
                 // (group B in slot 2j, group A in slot 2j+1).
                 auto slot_loads = [&](int j) __attribute__((always_inline)) {  // the loads of slot 2j; buffer indices are runtime here
-                    issue_k(j + 2, j & 1);
-                    issue_v(j + 1, (j + 1) & 1);
+                    issue_tiles(j + 2, j & 1, j + 1, (j + 1) & 1);
                 };
                 auto cluster_v = [&](int j) __attribute__((always_inline)) {
                     if (tile_active(j + 1)) softmax_tile(s, pk, (j + 1) * BN);
@@ -735,16 +750,13 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
                 u32x4 none;
                 // group A: K(j+2) -> K buffer j&1;  group B: V(j+1) -> V buffer (j+1)&1
                 auto group_loads = [&](int j) __attribute__((always_inline)) {
-                    if (!grp_b) {
-                        if (j + 2 < nkt) {
+                    const int jt = grp_b ? j + 1 : j + 2;
+                    if (jt < nkt) {
+                        const int kt0 = jt * BN;
+                        const bool whole = kt0 + BN <= N;
+                        char* dst = grp_b ? smem_b + ((j + 1) & 1) * 2 * TILE_BYTES + TILE_BYTES : smem_b + (j & 1) * 2 * TILE_BYTES;
 #pragma unroll
-                            for (int q = 0; q < LLD; ++q) issue_piece(lnt_c, Kh, goff_grp, lwave, j + 2, smem_b + (j & 1) * 2 * TILE_BYTES, q, none);
-                        }
-                    } else {
-                        if (j + 1 < nkt) {
-#pragma unroll
-                            for (int q = 0; q < LLD; ++q) issue_piece(lnt_c, Vh, goff_grp, lwave, j + 1, smem_b + ((j + 1) & 1) * 2 * TILE_BYTES + TILE_BYTES, q, none);
-                        }
+                        for (int q = 0; q < LLD; ++q) issue_piece(lnt_c, whole, grp_b ? Vh : Kh, goff_grp, lwave, kt0, dst, q, none);
                     }
                 };
                 auto cluster_x = [&](auto par_c, int j) __attribute__((always_inline)) {  // par = j & 1

@@ -103,22 +103,22 @@ class SearchResult:
         return sorted(self.times.items(), key=lambda kv: kv[1])
 
 
-def anneal(lat: Lattice, x0: Coords, measure: Callable[[Coords], float],
-           admit: Callable[[Coords], bool], seed: int = 0, t_max: float = 0.05,
-           t_min: float = 5e-4, cool: float = 1.05, remeasure: bool = False,
-           log: Optional[Callable[[Step], None]] = None) -> SearchResult:
-    """Simulated annealing of Alg. 1.  `measure(x)` returns a runtime (any unit), `admit(x)`
-    says whether x passed the probabilistic test.  x0 must be admitted."""
-    if x0 not in lat.points:
-        raise ValueError("x0 is not a point of the lattice")
+def anneal_states(x0, propose: Callable, measure: Callable, admit: Callable, key: Callable = lambda x: x,
+                  seed: int = 0, t_max: float = 0.05, t_min: float = 5e-4, cool: float = 1.05,
+                  remeasure: bool = False, log: Optional[Callable[[Step], None]] = None) -> SearchResult:
+    """Simulated annealing of Alg. 1 over any kind of schedule.  `propose(x, rng)` is the
+    mutation policy (returns a neighbour of x, or None if x has none), `measure(x)` returns a
+    runtime (any unit), `admit(x)` says whether x passed the probabilistic test, `key(x)` is a
+    hashable identity of a schedule (measurements and test verdicts are remembered per key).
+    x0 must be admitted."""
     if not (t_max > t_min > 0 and cool > 1):
         raise ValueError("need t_max > t_min > 0 and cool > 1")
     rng = random.Random(seed)
     if not admit(x0):
         raise ValueError("the initial schedule fails its own admission test")
     t0 = float(measure(x0))
-    times: Dict[Coords, float] = {x0: t0}
-    admitted: Dict[Coords, bool] = {x0: True}
+    times = {key(x0): t0}
+    admitted = {key(x0): True}
     res = SearchResult(seed=seed, t0=t0, x0=x0, best=x0, t_best=t0, final=x0, t_final=t0, times=times)
 
     def energy(t: float) -> float:
@@ -129,21 +129,22 @@ def anneal(lat: Lattice, x0: Coords, measure: Callable[[Coords], float],
     temp = t_max
     n = 0
     while temp > t_min:
-        cand = mutate(lat, x, rng)
+        cand = propose(x, rng)
         if cand is None:
             break
-        if cand not in admitted:
-            admitted[cand] = bool(admit(cand))
-            if not admitted[cand]:
+        kc = key(cand)
+        if kc not in admitted:
+            admitted[kc] = bool(admit(cand))
+            if not admitted[kc]:
                 res.rejected.append(cand)
-        ok = admitted[cand]
+        ok = admitted[kc]
         accepted = False
         t_c = fb = de = None
         r = rng.random()                       # drawn every step: the trajectory depends on the seed only
         if ok:
-            if remeasure or cand not in times:
-                times[cand] = float(measure(cand))
-            t_c = times[cand]
+            if remeasure or kc not in times:
+                times[kc] = float(measure(cand))
+            t_c = times[kc]
             fb = (t_x - t_c) / t0              # Eq. 1
             de = energy(t_c) - energy(t_x)     # = -fb
             if de < 0:
@@ -163,6 +164,17 @@ def anneal(lat: Lattice, x0: Coords, measure: Callable[[Coords], float],
         n += 1
     res.best, res.t_best = best, t_best
     return res
+
+
+def anneal(lat: Lattice, x0: Coords, measure: Callable[[Coords], float],
+           admit: Callable[[Coords], bool], seed: int = 0, t_max: float = 0.05,
+           t_min: float = 5e-4, cool: float = 1.05, remeasure: bool = False,
+           log: Optional[Callable[[Step], None]] = None) -> SearchResult:
+    """Alg. 1 over the variant lattice: `anneal_states` with the one-coordinate mutation."""
+    if x0 not in lat.points:
+        raise ValueError("x0 is not a point of the lattice")
+    return anneal_states(x0, lambda x, rng: mutate(lat, x, rng), measure, admit, seed=seed, t_max=t_max,
+                         t_min=t_min, cool=cool, remeasure=remeasure, log=log)
 
 
 # ------------------------------------------------------------------ GPU-side callables
