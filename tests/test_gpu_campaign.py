@@ -1,0 +1,67 @@
+"""Randomised test campaign of the library's default kernels against the fp64 oracle (the
+probabilistic testing of Sec. 4.2 / Sec. 5.2, with the oracle in the place of the unmodified
+kernel).  Every sample draws a shape, a dtype, a mask, an input family and a seed; the
+number of samples comes from ATTN_CAMPAIGN_SAMPLES (default 120: a few seconds).  Run as a
+script for a long campaign:  ATTN_CAMPAIGN_SAMPLES=5000 python -m pytest tests/test_gpu_campaign.py -m gpu -s
+"""
+import os
+import random
+import time
+
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_2403_16863_amd import inputs as I
+from tests.gpu_util import O_TOL, LSE_RTOL, run_gpu
+
+FAMILIES = ("normal", "normal", "normal", "wide", "peaked", "equal_scores", "large_negative",
+            "single_v_row", "signed_zero", "max_finite_v")
+# sequence lengths around every tile boundary of the shipped variants, plus odd ones
+LENGTHS = (1, 2, 17, 31, 32, 33, 63, 64, 65, 100, 127, 128, 129, 191, 192, 193, 255, 256, 257, 300, 383, 384,
+           385, 511, 512, 513, 640, 777, 1000, 1024, 1025)
+
+
+def draw(rng):
+    d = rng.choice((64, 128))
+    dtype = rng.choice((I.F16, I.BF16))
+    causal = rng.random() < 0.6
+    N = rng.choice(LENGTHS)
+    B = rng.choice((1, 1, 2, 3))
+    H = rng.choice((1, 2, 3, 5, 8))
+    if B * H * N > 16384:                       # keeps one oracle call well under a second
+        B, H = 1, max(1, 8192 // N)
+    return B, H, N, d, dtype, causal, rng.choice(FAMILIES), rng.randrange(1 << 30)
+
+
+@pytest.mark.gpu
+def test_campaign_against_oracle():
+    samples = int(os.environ.get("ATTN_CAMPAIGN_SAMPLES", "120"))
+    rng = random.Random(int(os.environ.get("ATTN_CAMPAIGN_SEED", "2024")))
+    worst_o, worst_l, t0 = 0.0, 0.0, time.time()
+    by_family = {}
+    for n in range(samples):
+        B, H, N, d, dtype, causal, fam, seed = draw(rng)
+        if fam in ("normal", "wide"):
+            w = I.Workload("c", B, H, N, d, causal, dtype, qk_sigma=2.0 if fam == "wide" else 1.0,
+                           v_dist="uniform" if fam == "wide" else "normal")
+            qb, kb, vb = I.make_qkv(w, seed)
+        else:
+            qb, kb, vb = I.make_adversarial(fam, B, H, N, d, dtype, seed)
+        scale = float(np.float32(1.0) / np.sqrt(np.float32(d)))
+        O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, causal, scale, dtype)
+        O, l = run_gpu(qb, kb, vb, causal, scale, dtype)
+        out_scale = max(1.0, float(np.abs(I.bits_to_f64(vb, dtype)).max())) if fam == "max_finite_v" else 1.0
+        what = f"sample {n}: B{B} H{H} N{N} d{d} dtype{dtype} causal{causal} {fam} seed{seed}"
+        assert np.isfinite(O).all() and np.isfinite(l).all(), what
+        eo = float(np.max(np.abs(O - O_ref))) / out_scale
+        el = float(np.max(np.abs(l - l_ref) / np.maximum(1.0, np.abs(l_ref))))
+        assert eo <= O_TOL[dtype], f"{what}: max|dO| = {eo:.3e}"
+        assert el <= LSE_RTOL, f"{what}: lse error {el:.3e}"
+        worst_o = max(worst_o, eo / O_TOL[dtype])
+        worst_l = max(worst_l, el / LSE_RTOL)
+        by_family[fam] = by_family.get(fam, 0) + 1
+        if (n + 1) % 500 == 0:
+            print(f"campaign: {n + 1} samples passed, {time.time() - t0:.0f} s", flush=True)
+    print(f"campaign: {samples} samples passed in {time.time() - t0:.1f} s; worst error as a fraction of the "
+          f"tolerance: O {worst_o:.3f}, lse {worst_l:.3f}; families {by_family}", flush=True)
