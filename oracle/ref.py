@@ -13,16 +13,17 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "attn_ref.cpp")
+_SRCS = [_SRC, os.path.join(_HERE, "gemm_ref.cpp")]
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with the host compiler (no HIP involved)."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS)
     if force or stale:
         subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-pthread",
-                               "-o", _LIB, _SRC])
+                               "-o", _LIB, *_SRCS])
     return _LIB
 
 
@@ -42,6 +43,9 @@ def lib():
         L.attn_ref_probs_f64.argtypes = [u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                          ctypes.c_int, ctypes.c_int, ctypes.c_double,
                                          ctypes.c_int, ctypes.c_longlong, f64p]
+        L.gemm_lrelu_ref_f64.restype = ctypes.c_int
+        L.gemm_lrelu_ref_f64.argtypes = [u16p, u16p, f64p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                         ctypes.c_double, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
         L.attn_ref_decode.restype = ctypes.c_double
         L.attn_ref_decode.argtypes = [ctypes.c_uint16, ctypes.c_int]
         _lib = L
@@ -99,3 +103,20 @@ def attn_ref_probs(q, k, causal: bool, scale: float, dtype: int, row: int):
 
 def decode(bits: int, dtype: int) -> float:
     return lib().attn_ref_decode(int(bits), int(dtype))
+
+
+def gemm_lrelu_ref(a, b, slope: float, dtype: int, nthreads: int = 0):
+    """C = leaky_relu(A B) in float64.  a: uint16 [M,K], b: uint16 [K,N].  Returns (C [M,N], threads_used)."""
+    a, ap = _u16(a)
+    b, bp = _u16(b)
+    if a.ndim != 2 or b.ndim != 2 or a.shape[1] != b.shape[0]:
+        raise ValueError("a must be [M,K] and b [K,N]")
+    M, K = a.shape
+    N = b.shape[1]
+    out = np.empty((M, N), dtype=np.float64)
+    used = ctypes.c_int(0)
+    rc = lib().gemm_lrelu_ref_f64(ap, bp, out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), M, N, K,
+                                  float(slope), int(dtype), int(nthreads), ctypes.byref(used))
+    if rc != 0:
+        raise ValueError(f"gemm_lrelu_ref_f64 rejected its arguments (rc={rc})")
+    return out, used.value
