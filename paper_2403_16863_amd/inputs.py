@@ -168,3 +168,46 @@ def sample_rows(w: Workload, count: int, seed: int, edges=(31, 32, 63, 64, 127, 
         need = count - len(rows)
         rows.update(int(r) for r in g.integers(0, total, size=need))
     return np.array(sorted(rows), dtype=np.int64)
+
+
+# ---- second workload: fused GEMM + LeakyReLU (Sec. 5, Table 3).  The paper's input is a shape
+# (M, N, K = 512, 512, 2048, binary16) filled with random tensors; the slope is not stated.
+GEMM_M, GEMM_N, GEMM_K = 512, 512, 2048
+GEMM_SLOPE = 0.01
+GEMM_FAMILIES = ("normal", "positive", "cancelling", "signed_zero", "large", "one_hot")
+
+
+def make_gemm(M: int, N: int, K: int, dtype: int, seed: int, family: str = "normal"):
+    """Return (a [M,K], b [K,N]) as uint16 bit patterns.  "normal": iid N(0,1), the sum over K then
+    has both signs, so both branches of the activation are taken.  The other families stress
+    one thing each: "positive" (no negative output), "cancelling" (pairs of equal and opposite
+    products: outputs near zero from large terms), "signed_zero" (half of the entries +-0),
+    "large" (|x| around 2^7: sums near the top of binary16's range), "one_hot" (each row of A has
+    a single 1: C is a row gather of B, exact)."""
+    g = _rng(seed, 21)
+    a = g.standard_normal((M, K), dtype=np.float32)
+    b = g.standard_normal((K, N), dtype=np.float32)
+    if family == "normal":
+        pass
+    elif family == "positive":
+        a, b = np.abs(a), np.abs(b)
+    elif family == "cancelling":
+        h = K // 2
+        if h:
+            a[:, h:2 * h] = -a[:, :h] * np.float32(64.0)
+            a[:, :h] *= np.float32(64.0)
+            b[h:2 * h, :] = b[:h, :]
+    elif family == "signed_zero":
+        za = g.random((M, K), dtype=np.float32) < 0.5
+        zb = g.random((K, N), dtype=np.float32) < 0.5
+        a[za] = -0.0
+        b[zb] = 0.0
+    elif family == "large":
+        a *= np.float32(8.0)
+        b *= np.float32(8.0)
+    elif family == "one_hot":
+        a[:] = 0.0
+        a[np.arange(M), g.integers(0, K, size=M)] = 1.0
+    else:
+        raise ValueError(family)
+    return f32_to_bits(a, dtype), f32_to_bits(b, dtype)

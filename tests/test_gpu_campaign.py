@@ -40,6 +40,8 @@ def test_campaign_against_oracle():
     rng = random.Random(int(os.environ.get("ATTN_CAMPAIGN_SEED", "2024")))
     worst_o, worst_l, t0 = 0.0, 0.0, time.time()
     by_family = {}
+    trace = os.environ.get("ATTN_CAMPAIGN_TRACE")  # file that names the sample in flight, for a run that dies
+    print(f"campaign: {samples} samples to draw", flush=True)
     for n in range(samples):
         B, H, N, d, dtype, causal, fam, seed = draw(rng)
         if fam in ("normal", "wide"):
@@ -50,6 +52,9 @@ def test_campaign_against_oracle():
             qb, kb, vb = I.make_adversarial(fam, B, H, N, d, dtype, seed)
         scale = float(np.float32(1.0) / np.sqrt(np.float32(d)))
         O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, causal, scale, dtype)
+        if trace:
+            with open(trace, "w") as f:
+                f.write(f"sample {n}: B{B} H{H} N{N} d{d} dtype{dtype} causal{causal} {fam} seed{seed}\n")
         O, l = run_gpu(qb, kb, vb, causal, scale, dtype)
         out_scale = max(1.0, float(np.abs(I.bits_to_f64(vb, dtype)).max())) if fam == "max_finite_v" else 1.0
         what = f"sample {n}: B{B} H{H} N{N} d{d} dtype{dtype} causal{causal} {fam} seed{seed}"
@@ -61,7 +66,7 @@ def test_campaign_against_oracle():
         worst_o = max(worst_o, eo / O_TOL[dtype])
         worst_l = max(worst_l, el / LSE_RTOL)
         by_family[fam] = by_family.get(fam, 0) + 1
-        if (n + 1) % 500 == 0:
+        if (n + 1) % 250 == 0:
             print(f"campaign: {n + 1} samples passed, {time.time() - t0:.0f} s", flush=True)
     print(f"campaign: {samples} samples passed in {time.time() - t0:.1f} s; worst error as a fraction of the "
           f"tolerance: O {worst_o:.3f}, lse {worst_l:.3f}; families {by_family}", flush=True)
