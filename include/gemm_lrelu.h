@@ -45,7 +45,8 @@ int gemm_lrelu_num_variants(void);
 int gemm_lrelu_default_variant(int M, int N, int K);
 
 /* Knobs of a variant, in this order: "wk" (waves per workgroup; they split K), "bkw" (k extent a
- * wave loads per pipeline stage), "stages" (stages of each wave's LDS ring).  knobs: host, 3 ints. */
+ * wave loads per pipeline stage), "stages" (stages of each wave's LDS ring), "rot" (1: the workgroups of an XCD start at
+ * different k and wrap around, so that their L2 misses do not coincide).  knobs: host, 4 ints. */
 int gemm_lrelu_variant_knobs(int variant_id, int* knobs);
 
 /* Timing aid for the search and the benchmark: `warmup` untimed launches, then `iters` launches

@@ -63,11 +63,12 @@ __host__ __device__ inline void tile_of_block(int b, int ntm, int ntn, int& tm, 
     tn = panel * GW + r % w;
 }
 
-template <int WK_, int BKW_, int S_>
+template <int WK_, int BKW_, int S_, int ROT_>
 struct Knobs {
     static constexpr int WK = WK_;    // waves per workgroup, splitting K
     static constexpr int BKW = BKW_;  // k extent of one stage of one wave
     static constexpr int S = S_;      // stages in a wave's ring
+    static constexpr int ROT = ROT_;  // 1: every workgroup of an XCD starts at another k (see the kernel)
 };
 
 // A piece in LDS: 32 rows of CPA 16-byte chunks, read row-wise (lane = row).  The chunk index is
@@ -84,7 +85,7 @@ __device__ __forceinline__ int b_code(int row) { return (row >> 1) & 1; }
 
 template <class T, class KN>
 __global__ __launch_bounds__(KN::WK * 64) void gemm_lrelu_kernel(Params p) {
-    constexpr int WK = KN::WK, BKW = KN::BKW, S = KN::S;
+    constexpr int WK = KN::WK, BKW = KN::BKW, S = KN::S, ROT = KN::ROT;
     constexpr int CPA = BKW / 8;    // chunks per row of the A piece
     constexpr int RBA = BKW * 2;    // bytes per row of the A piece
     constexpr int A_BYTES = 32 * RBA;
@@ -135,7 +136,16 @@ __global__ __launch_bounds__(KN::WK * 64) void gemm_lrelu_kernel(Params p) {
     // this wave's k ranges: t = 0 .. nkt-1 with  k0 = (t*WK + wk) * BKW < K
     const int nkt = K > wk * BKW ? (K - wk * BKW + WK * BKW - 1) / (WK * BKW) : 0;
 
+    // Rotation: the workgroups of one XCD share rows of A and columns of B through that XCD's L2.
+    // Started together at k = 0 they all ask for the same lines at the same time, and the L2
+    // has only as many distinct lines on order as ONE ring is deep.  With ROT the i-th workgroup
+    // of an XCD walks its ranges from i/32 of the way through (and wraps around): a line is
+    // still fetched into the L2 once, but the misses of 32 rings are in flight side by side.
+    const int rot = ROT ? (int)(((blockIdx.x >> 3) & 31) * (unsigned)nkt) >> 5 : 0;
+
     auto issue = [&](int t, int stage) __attribute__((always_inline)) {
+        t += rot;
+        if (t >= nkt) t -= nkt;
         const int k0 = (t * WK + wk) * BKW;
         char* st = ring + stage * STAGE;
         const char* ab = pa + (size_t)k0 * 2;
@@ -249,27 +259,34 @@ __global__ __launch_bounds__(KN::WK * 64) void gemm_lrelu_kernel(Params p) {
 // ---- host side -----------------------------------------------------------------------------
 typedef void (*KernelFn)(Params);
 struct Variant {
-    int wk, bkw, stages;
+    int wk, bkw, stages, rot;
     KernelFn fn[2];  // by dtype
 };
-#define GEMM_VARIANT(WK, BKW, S) \
-    { WK, BKW, S, { gemm_lrelu_kernel<attn::F16, Knobs<WK, BKW, S>>, gemm_lrelu_kernel<attn::BF16, Knobs<WK, BKW, S>> } }
+#define GEMM_VARIANT(WK, BKW, S, ROT) \
+    { WK, BKW, S, ROT, { gemm_lrelu_kernel<attn::F16, Knobs<WK, BKW, S, ROT>>, gemm_lrelu_kernel<attn::BF16, Knobs<WK, BKW, S, ROT>> } }
 static const Variant kVariants[] = {
-    GEMM_VARIANT(4, 32, 8),   // 0
-    GEMM_VARIANT(4, 32, 4),   // 1
-    GEMM_VARIANT(4, 32, 10),  // 2
-    GEMM_VARIANT(4, 64, 4),   // 3
-    GEMM_VARIANT(4, 64, 3),   // 4
-    GEMM_VARIANT(8, 32, 4),   // 5
-    GEMM_VARIANT(8, 32, 3),   // 6
-    GEMM_VARIANT(2, 64, 8),   // 7
-    GEMM_VARIANT(2, 64, 4),   // 8
-    GEMM_VARIANT(2, 32, 8),   // 9
-    GEMM_VARIANT(1, 64, 8),   // 10
-    GEMM_VARIANT(2, 32, 4),   // 11
+    GEMM_VARIANT(4, 32, 8, 0),   // 0
+    GEMM_VARIANT(4, 32, 4, 0),   // 1
+    GEMM_VARIANT(4, 32, 10, 0),  // 2
+    GEMM_VARIANT(4, 64, 4, 0),   // 3
+    GEMM_VARIANT(4, 64, 3, 0),   // 4
+    GEMM_VARIANT(8, 32, 4, 0),   // 5
+    GEMM_VARIANT(8, 32, 3, 0),   // 6
+    GEMM_VARIANT(2, 64, 8, 0),   // 7
+    GEMM_VARIANT(2, 64, 4, 0),   // 8
+    GEMM_VARIANT(2, 32, 8, 0),   // 9
+    GEMM_VARIANT(1, 64, 8, 0),   // 10
+    GEMM_VARIANT(2, 32, 4, 0),   // 11
+    GEMM_VARIANT(4, 32, 4, 1),   // 12
+    GEMM_VARIANT(4, 32, 8, 1),   // 13
+    GEMM_VARIANT(4, 64, 3, 1),   // 14
+    GEMM_VARIANT(4, 64, 4, 1),   // 15
+    GEMM_VARIANT(8, 32, 3, 1),   // 16
+    GEMM_VARIANT(8, 32, 4, 1),   // 17
+    GEMM_VARIANT(4, 32, 3, 0),   // 18
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
-constexpr int kDefault = 0;
+constexpr int kDefault = 1;
 
 static int check_args(const void* a, const void* b, const void* c, int M, int N, int K, int dtype, int variant_id) {
     if (!a || !b || !c) return GEMM_EINVAL;
@@ -318,6 +335,7 @@ int gemm_lrelu_variant_knobs(int variant_id, int* knobs) {
     knobs[0] = gemm::kVariants[variant_id].wk;
     knobs[1] = gemm::kVariants[variant_id].bkw;
     knobs[2] = gemm::kVariants[variant_id].stages;
+    knobs[3] = gemm::kVariants[variant_id].rot;
     return GEMM_OK;
 }
 

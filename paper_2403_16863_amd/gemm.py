@@ -12,7 +12,7 @@ from . import binding
 
 GEMM_F16, GEMM_BF16 = 0, 1
 GEMM_OK, GEMM_EINVAL, GEMM_ELAUNCH = 0, -1, -2
-KNOB_NAMES = ("wk", "bkw", "stages")
+KNOB_NAMES = ("wk", "bkw", "stages", "rot")
 
 # every symbol include/gemm_lrelu.h declares
 SYMBOLS = ("gemm_lrelu", "gemm_lrelu_variant", "gemm_lrelu_num_variants", "gemm_lrelu_default_variant",
@@ -111,8 +111,8 @@ def gemm_lrelu_default_variant(M: int, N: int, K: int) -> int:
 
 
 def gemm_lrelu_variant_knobs(variant_id: int):
-    """(wk, bkw, stages) of a variant."""
-    buf = (ctypes.c_int * 3)()
+    """(wk, bkw, stages, rot) of a variant."""
+    buf = (ctypes.c_int * 4)()
     rc = lib().gemm_lrelu_variant_knobs(int(variant_id), buf)
     if rc != GEMM_OK:
         raise GemmError(rc, "gemm_lrelu_variant_knobs")

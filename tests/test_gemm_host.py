@@ -51,11 +51,11 @@ def test_variant_table():
     assert nv >= 4
     seen = set()
     for v in range(nv):
-        wk, bkw, stages = gemm.gemm_lrelu_variant_knobs(v)
+        wk, bkw, stages, rot = gemm.gemm_lrelu_variant_knobs(v)
         assert wk in (1, 2, 4, 8) and bkw in (32, 64) and stages >= 3
         assert wk * stages * bkw * 128 <= 160 * 1024        # LDS of one workgroup
-        assert (wk, bkw, stages) not in seen
-        seen.add((wk, bkw, stages))
+        assert rot in (0, 1) and (wk, bkw, stages, rot) not in seen
+        seen.add((wk, bkw, stages, rot))
     assert 0 <= gemm.gemm_lrelu_default_variant(512, 512, 2048) < nv
     with pytest.raises(gemm.GemmError):
         gemm.gemm_lrelu_variant_knobs(nv)

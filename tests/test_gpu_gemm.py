@@ -171,3 +171,15 @@ def test_binding_rejects_what_the_boundary_cannot_take():
         gemm.gemm_lrelu(a[:, :60].contiguous(), b[:60].contiguous(), c, 0.1)   # K = 60
     with pytest.raises(gemm.GemmError):
         gemm.gemm_lrelu_variant(a, b, c, 0.1, 999)
+
+
+def test_admission_test_and_a_short_search():
+    """Every shipped variant passes the probabilistic test against the default kernel, and a short
+    annealing run on the paper's shape ends on an admitted variant that is no slower than the start."""
+    from paper_2403_16863_amd import gemm, gemm_search as GS
+    for v in all_variants():
+        assert GS.admit_against_default(v, I.F16, samples=6, seed=1), f"variant {v}"
+    assert GS.admit_against_default(gemm.gemm_lrelu_default_variant(512, 512, 2048), I.BF16, samples=6, seed=2)
+    res, table = GS.search(seed=3, cool=1.3)
+    assert res.best in table and res.t_best <= res.t0 and len(res.steps) >= 10
+    assert not res.rejected
