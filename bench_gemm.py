@@ -18,8 +18,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` runs (see profiles/); None until measured
-MEASURED_HBM_BYTES = None
+# Bytes per launch that cross the L2 boundary, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE`
+# runs of this script scaled by the same counters on a 256 MiB device copy (FETCH_SIZE counts
+# 2 KiB, WRITE_SIZE 1 KiB); default variant, binary16.  Written up under profiles/.
+MEASURED_HBM_BYTES = (6185.0 * 2.0 + 512.0 * 1.0) * 1024
 
 
 def main():
@@ -78,7 +80,7 @@ def main():
         "latency_us_with_python_launch": wall_us,
         "launch_floor_us": floor_us,
         "roofline": {"bound": "hbm", "achieved": alg_bytes / dev_us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": alg_bytes / dev_us / 1e3 / HBM_PEAK_GBS, "traffic": MEASURED_HBM_BYTES,
+                     "frac": alg_bytes / dev_us / 1e3 / HBM_PEAK_GBS, "traffic": MEASURED_HBM_BYTES if (args.variant is None and dtype == I.F16) else None,
                      "algorithmic_bytes": alg_bytes,
                      "note": "launches back to back; a launch that does no work takes launch_floor_us of it"},
     }
