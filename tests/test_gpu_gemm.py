@@ -183,3 +183,15 @@ def test_admission_test_and_a_short_search():
     res, table = GS.search(seed=3, cool=1.3)
     assert res.best in table and res.t_best <= res.t0 and len(res.steps) >= 10
     assert not res.rejected
+
+
+def test_strategy_comparison_runs_on_the_measured_table():
+    from paper_2403_16863_amd import search_compare as SC
+    label, names, keys, start, measure, admit, unit = SC.gemm_space()
+    keys = keys[:6] + [start] if start not in keys[:6] else keys[:6]
+    table, rejected = SC.measure_table(keys, measure, admit, reps=3)
+    assert not rejected and all(len(v) == 3 and min(v) > 0 for v in table.values())
+    res = SC.compare(table, start, budgets=(3, 12), seeds=5)
+    assert set(res) == set(SC.STRATEGIES) and all(r["mean_regret"] >= 0 for rows in res.values() for r in rows)
+    att = SC.attribution(table, names)
+    assert set(att["knobs"]) == set(names)
