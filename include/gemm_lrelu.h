@@ -54,6 +54,21 @@ int gemm_lrelu_variant_knobs(int variant_id, int* knobs);
 int gemm_lrelu_time(const void* a, const void* b, void* c, int M, int N, int K, float slope, int dtype,
                     void* stream, int variant_id, int warmup, int iters, float* ms_total);
 
+/* Kernels loaded from code objects: the instruction-level schedule search (Sec. 3.1 to 3.3) takes
+ * the compiled kernel of a variant, moves memory instructions in its assembly, assembles the result
+ * and runs it through these.  `path` names a gfx950 code object file (host string), `kernel_name`
+ * the kernel symbol in it; the kernel must take the arguments, launch shape and LDS of variant
+ * `variant_id` for element type `dtype`.  Returns a handle >= 0 (at most 64 are open at a time;
+ * GEMM_EINVAL when the table is full), or a negative error.  Unload only after the work that
+ * uses the handle has finished. */
+int gemm_lrelu_codeobj_load(const char* path, const char* kernel_name, int variant_id, int dtype);
+int gemm_lrelu_codeobj_unload(int handle);
+/* gemm_lrelu / gemm_lrelu_time with the loaded kernel in place of the built-in one. */
+int gemm_lrelu_codeobj(int handle, const void* a, const void* b, void* c, int M, int N, int K, float slope, int dtype,
+                       void* stream);
+int gemm_lrelu_time_codeobj(int handle, const void* a, const void* b, void* c, int M, int N, int K, float slope,
+                            int dtype, void* stream, int warmup, int iters, float* ms_total);
+
 /* The tile of C that workgroup `block` of `nblocks` computes (host logic, no GPU needed): tiles
  * are 32 x 32; ntm = ceil(M / 32), ntn = ceil(N / 32), nblocks = ntm * ntn.  Workgroups are
  * placed round-robin on the 8 XCDs; the map gives each XCD a contiguous run of tiles, ordered in

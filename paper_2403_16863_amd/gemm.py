@@ -16,7 +16,8 @@ KNOB_NAMES = ("wk", "bkw", "stages", "rot")
 
 # every symbol include/gemm_lrelu.h declares
 SYMBOLS = ("gemm_lrelu", "gemm_lrelu_variant", "gemm_lrelu_num_variants", "gemm_lrelu_default_variant",
-           "gemm_lrelu_variant_knobs", "gemm_lrelu_time", "gemm_lrelu_tile_of_block")
+           "gemm_lrelu_variant_knobs", "gemm_lrelu_time", "gemm_lrelu_tile_of_block", "gemm_lrelu_codeobj_load",
+           "gemm_lrelu_codeobj_unload", "gemm_lrelu_codeobj", "gemm_lrelu_time_codeobj")
 
 _ready = False
 
@@ -48,6 +49,14 @@ def lib():
         L.gemm_lrelu_variant_knobs.argtypes = [i, ctypes.POINTER(i)]
         L.gemm_lrelu_tile_of_block.restype = i
         L.gemm_lrelu_tile_of_block.argtypes = [i, i, i, ctypes.POINTER(i), ctypes.POINTER(i)]
+        L.gemm_lrelu_codeobj_load.restype = i
+        L.gemm_lrelu_codeobj_load.argtypes = [ctypes.c_char_p, ctypes.c_char_p, i, i]
+        L.gemm_lrelu_codeobj_unload.restype = i
+        L.gemm_lrelu_codeobj_unload.argtypes = [i]
+        L.gemm_lrelu_codeobj.restype = i
+        L.gemm_lrelu_codeobj.argtypes = [i] + common
+        L.gemm_lrelu_time_codeobj.restype = i
+        L.gemm_lrelu_time_codeobj.argtypes = [i] + common + [i, i, ctypes.POINTER(f)]
         _ready = True
     return L
 
@@ -126,3 +135,33 @@ def gemm_lrelu_tile_of_block(block: int, ntm: int, ntn: int):
     if rc != GEMM_OK:
         raise GemmError(rc, "gemm_lrelu_tile_of_block")
     return tm.value, tn.value
+
+
+def gemm_lrelu_codeobj_load(path: str, kernel_name: str, variant_id: int, dtype: int) -> int:
+    """Handle of a kernel loaded from a gfx950 code object, standing in for variant `variant_id`."""
+    h = lib().gemm_lrelu_codeobj_load(path.encode(), kernel_name.encode(), int(variant_id), int(dtype))
+    if h < 0:
+        raise GemmError(h, "gemm_lrelu_codeobj_load")
+    return h
+
+
+def gemm_lrelu_codeobj_unload(handle: int) -> None:
+    rc = lib().gemm_lrelu_codeobj_unload(int(handle))
+    if rc != GEMM_OK:
+        raise GemmError(rc, "gemm_lrelu_codeobj_unload")
+
+
+def gemm_lrelu_codeobj(handle: int, a, b, c, slope: float, stream=None) -> None:
+    args, dt, st = _marshal(a, b, c, stream)
+    rc = lib().gemm_lrelu_codeobj(int(handle), *args, float(slope), dt, st)
+    if rc != GEMM_OK:
+        raise GemmError(rc, "gemm_lrelu_codeobj")
+
+
+def gemm_lrelu_time_codeobj(handle: int, a, b, c, slope: float, warmup: int = 5, iters: int = 100, stream=None) -> float:
+    args, dt, st = _marshal(a, b, c, stream)
+    ms = ctypes.c_float(0.0)
+    rc = lib().gemm_lrelu_time_codeobj(int(handle), *args, float(slope), dt, st, int(warmup), int(iters), ctypes.byref(ms))
+    if rc != GEMM_OK:
+        raise GemmError(rc, "gemm_lrelu_time_codeobj")
+    return float(ms.value)

@@ -17,7 +17,7 @@ def test_every_declared_symbol_is_exported_and_bound():
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = sorted(set(re.findall(r"\b(gemm_lrelu[a-z_0-9]*)\s*\(", text)))
     L = gemm.lib()
-    assert len(names) == 7
+    assert len(names) == 11
     for n in names:
         assert hasattr(L, n), f"libattn.so does not export {n}"
         assert hasattr(gemm, n), f"binding has no function {n}"

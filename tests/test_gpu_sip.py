@@ -79,3 +79,49 @@ def test_short_search_winner_passes_the_oracle():
         A.attn_codeobj_unload(h)
     finally:
         shutil.rmtree(d, ignore_errors=True)
+
+
+def test_gemm_code_object_path_and_a_short_search():
+    """Second workload: the unmodified kernel loaded from its own assembly reproduces the library
+    kernel bit for bit; a short annealing run over instruction positions ends on a kernel that
+    passed the test against the unmodified one, and that kernel also passes the fp64 oracle."""
+    import torch
+    from oracle import ref
+    from paper_2403_16863_amd import gemm as G, gemm_search as GS, inputs as I, sip
+    from tests.test_gpu_gemm import check
+    variant = G.gemm_lrelu_default_variant(I.GEMM_M, I.GEMM_N, I.GEMM_K)
+    d = tempfile.mkdtemp(prefix="sip_gemm_gpu_")
+    try:
+        k = sip.Kernel(sip.compile_gemm_base(d, I.F16, G.gemm_lrelu_variant_knobs(variant)), loop_depth=1)
+        run = sip.GemmRunner(k, variant, I.F16, d, samples=6, seed=1)
+        x0 = sip.Schedule(tuple(k.nodes))
+        assert run.admit(x0)                                   # bit-identical on six shapes
+        h = run.handle(x0)
+        a = torch.zeros((32, 64), dtype=torch.bfloat16, device="cuda")
+        with pytest.raises(G.GemmError):                       # loaded for binary16
+            G.gemm_lrelu_codeobj(h, a, a.t().contiguous(), torch.zeros((32, 32), dtype=torch.bfloat16, device="cuda"), 0.1)
+        with pytest.raises(G.GemmError):
+            G.gemm_lrelu_codeobj_load("/nonexistent.co", k.name, variant, I.F16)
+    finally:
+        shutil.rmtree(d, ignore_errors=True)
+    res = sip.search_gemm(seed=2, cool=1.25, samples=6, validate_rounds=2, keep_best=None)
+    assert res["steps"] >= 15 and res["admitted"] >= 1 and res["movable_instructions"] >= 10
+    assert res["best_us"] <= res["unmodified_codeobj_us"]
+    # the winner's assembly, reloaded, against the oracle on a ragged shape
+    d = tempfile.mkdtemp(prefix="sip_gemm_gpu_")
+    try:
+        best_s = d + "/best.s"
+        res = sip.search_gemm(seed=2, cool=1.25, samples=6, validate_rounds=1, keep_best=best_s)
+        text = open(best_s).read()
+        name = sip.Kernel(text, loop_depth=1).name
+        h = G.gemm_lrelu_codeobj_load(sip.assemble(text, d, "best"), name, variant, I.F16)
+        for (M, N, K) in ((100, 72, 328), (I.GEMM_M, I.GEMM_N, I.GEMM_K)):
+            ab, bb = I.make_gemm(M, N, K, I.F16, seed=8)
+            a, b = GS._device(ab, I.F16), GS._device(bb, I.F16)
+            c = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+            G.gemm_lrelu_codeobj(h, a, b, c, I.GEMM_SLOPE)
+            torch.cuda.synchronize()
+            check(c.to(torch.float64).cpu().numpy(), ab, bb, I.GEMM_SLOPE, I.F16, f"searched kernel M{M} N{N} K{K}")
+        G.gemm_lrelu_codeobj_unload(h)
+    finally:
+        shutil.rmtree(d, ignore_errors=True)

@@ -136,12 +136,13 @@ def test_wait_counter_bookkeeping():
     assert sip.try_move(k.nodes, _idx(k, "ds_read"), +1) is None   # the wait covered the read
     k = _mini(["s_waitcnt lgkmcnt(15)", "ds_read_b128 v[4:7], v1"])
     assert sip.try_move(k.nodes, _idx(k, "ds_read"), -1) is None   # counter field is full
-    k = _mini(["s_waitcnt vmcnt(0)", "ds_read_b128 v[4:7], v1"])
-    assert sip.try_move(k.nodes, _idx(k, "ds_read"), -1) is not None  # another counter: free to cross, unchanged
-    # a combined wait keeps its other field
-    k = _mini(["s_waitcnt vmcnt(0) lgkmcnt(1)", "ds_read_b128 v[4:7], v1"])
-    up = sip.try_move(k.nodes, _idx(k, "ds_read"), -1)
-    assert "vmcnt(0) lgkmcnt(2)" in up[_idx(k, "s_waitcnt") + 1].text
+    # a wait on the tile loads is what makes LDS contents valid (direct global->LDS loads, no
+    # barrier needed when the reader is the loader): an LDS read stays on its side of it
+    for wait in ("s_waitcnt vmcnt(0)", "s_waitcnt vmcnt(24)", "s_waitcnt vmcnt(0) lgkmcnt(1)"):
+        k = _mini([wait, "ds_read_b128 v[4:7], v1"])
+        assert sip.try_move(k.nodes, _idx(k, "ds_read"), -1) is None, wait
+        k = _mini(["ds_read_b128 v[4:7], v1", wait])
+        assert sip.try_move(k.nodes, _idx(k, "ds_read"), +1) is None, wait
 
 
 def test_tile_load_unit():
@@ -180,3 +181,37 @@ def test_anneal_states_on_a_toy_schedule():
     res2 = anneal_states(0, lambda x, rng: x + rng.choice((-1, 1)), lambda x: abs(x - 7) + 1.0,
                          lambda x: True, seed=5, t_max=0.5, t_min=1e-3, cool=1.03)
     assert [s.candidate for s in res.steps] == [s.candidate for s in res2.steps]   # deterministic per seed
+
+
+GEMM_KNOBS = (4, 32, 4, 0)
+
+
+def test_gemm_kernel_parses_and_mutates():
+    """The second workload's kernel: its steady-state loop is straight-line code at loop depth 1
+    holding the counted wait, six LDS reads, four tile loads and two MFMAs; moves keep the
+    multiset of instructions, never carry a read across the wait on the loads, and still assemble."""
+    d = tempfile.mkdtemp(prefix="sip_gemm_test_")
+    try:
+        text = sip.compile_gemm_base(d, 0, GEMM_KNOBS)
+        k = sip.Kernel(text, loop_depth=1)
+        assert k.render() == text
+        mov = [k.nodes[i] for i in sip.movable_positions(k.nodes)]
+        assert sum(n.kind == "unit" for n in mov) >= 4 and sum(n.mnem.startswith("ds_read") for n in mov) >= 6
+        rng = random.Random(1)
+        x = sip.Schedule(tuple(k.nodes))
+        for _ in range(300):
+            y = sip.propose(x, rng)
+            assert y is not None
+            x = y
+        assert sorted(_instr_lines(k.render(list(x.nodes)))) != [] and len(x.moves) == 300
+        strip = lambda ls: sorted(re.sub(r"lgkmcnt\(\d+\)", "lgkmcnt(n)", l) for l in ls)
+        assert strip(_instr_lines(k.render(list(x.nodes)))) == strip(_instr_lines(text))
+        # every LDS read of the loop is still behind the loop's wait on the loads
+        body = [n for n in x.nodes if n.in_loop and n.kind in ("ins", "unit")]
+        first_wait = next(i for i, n in enumerate(body) if n.mnem == "s_waitcnt" and "vmcnt" in n.text)
+        steady = body[:next(i for i, n in enumerate(body) if n.mnem.startswith("s_cbranch"))]
+        assert all(not n.mnem.startswith("ds_read") for n in steady[:first_wait])
+        assert sum(n.mnem.startswith("ds_read") for n in steady) == 6
+        sip.assemble(k.render(list(x.nodes)), d, "mut")
+    finally:
+        shutil.rmtree(d, ignore_errors=True)
