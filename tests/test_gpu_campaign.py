@@ -70,3 +70,38 @@ def test_campaign_against_oracle():
             print(f"campaign: {n + 1} samples passed, {time.time() - t0:.0f} s", flush=True)
     print(f"campaign: {samples} samples passed in {time.time() - t0:.1f} s; worst error as a fraction of the "
           f"tolerance: O {worst_o:.3f}, lse {worst_l:.3f}; families {by_family}", flush=True)
+
+
+@pytest.mark.gpu
+def test_gemm_campaign_against_oracle():
+    """The same for the second workload: shape (every size a multiple of 8 where the boundary asks for
+    it, around the 32-wide tile and the 32/64/128/256/512-wide k ranges), dtype, slope, input family,
+    variant and seed at random; element-wise against the fp64 oracle with the tolerance derived in
+    tests/test_gpu_gemm.py.  GEMM_CAMPAIGN_SAMPLES sets the count (default 60)."""
+    from paper_2403_16863_amd import gemm
+    from tests.test_gpu_gemm import check, run_gpu
+    samples = int(os.environ.get("GEMM_CAMPAIGN_SAMPLES", "60"))
+    rng = random.Random(int(os.environ.get("ATTN_CAMPAIGN_SEED", "2024")) + 1)
+    ms = (1, 2, 17, 31, 32, 33, 63, 64, 65, 100, 127, 128, 129, 200, 255, 256, 257, 300, 512)
+    ns = (8, 16, 24, 32, 40, 56, 64, 72, 96, 120, 128, 136, 256, 264, 512)
+    ks = (8, 16, 24, 32, 40, 56, 64, 72, 120, 128, 136, 248, 256, 264, 504, 512, 520, 1000, 1024, 1032, 2048)
+    nv = gemm.gemm_lrelu_num_variants()
+    worst, t0 = 0.0, time.time()
+    print(f"gemm campaign: {samples} samples to draw", flush=True)
+    for n in range(samples):
+        M, N, K = rng.choice(ms), rng.choice(ns), rng.choice(ks)
+        dtype = rng.choice((I.F16, I.BF16))
+        fam = rng.choice(I.GEMM_FAMILIES)
+        if fam == "large" and dtype == I.F16:
+            K = min(K, 1024)
+        slope = rng.choice((0.01, 0.01, 0.2, 0.0, 1.0, -0.5))
+        variant = rng.choice((None, rng.randrange(nv)))
+        seed = rng.randrange(1 << 30)
+        ab, bb = I.make_gemm(M, N, K, dtype, seed, fam)
+        what = f"gemm sample {n}: M{M} N{N} K{K} dtype{dtype} {fam} slope{slope} variant{variant} seed{seed}"
+        c = run_gpu(ab, bb, slope, dtype, variant)
+        worst = max(worst, check(c, ab, bb, slope, dtype, what))
+        if (n + 1) % 250 == 0:
+            print(f"gemm campaign: {n + 1} samples passed, {time.time() - t0:.0f} s", flush=True)
+    print(f"gemm campaign: {samples} samples passed in {time.time() - t0:.1f} s; worst error as a fraction of the "
+          f"tolerance: {worst:.3f}", flush=True)
