@@ -182,7 +182,7 @@ def make_gemm(M: int, N: int, K: int, dtype: int, seed: int, family: str = "norm
     has both signs, so both branches of the activation are taken.  The other families stress
     one thing each: "positive" (no negative output), "cancelling" (pairs of equal and opposite
     products: outputs near zero from large terms), "signed_zero" (half of the entries +-0),
-    "large" (|x| around 2^7: sums near the top of binary16's range), "one_hot" (each row of A has
+    "large" (entries scaled by 8: sums near the top of binary16's range), "one_hot" (each row of A has
     a single 1: C is a row gather of B, exact)."""
     g = _rng(seed, 21)
     a = g.standard_normal((M, K), dtype=np.float32)

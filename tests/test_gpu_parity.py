@@ -64,6 +64,26 @@ def test_benchmark_configs_sampled(idx, nrows):
     assert (np.abs(O) <= vmax * (1 + 1e-2) + 1e-3).all()
 
 
+@pytest.mark.parametrize("B,H,N,d,causal,dtype,nrows", [
+    (1, 1, 65536, 128, True, I.BF16, 256),      # one very long sequence: 256 query tiles of one head
+    (1, 2, 40000, 64, False, I.F16, 192),       # long, ragged (40000 = 625 * 64), no mask
+    (64, 64, 64, 64, True, I.F16, 1024),        # 4096 heads of one tile each: more work items than workgroups
+    (3, 37, 257, 128, True, I.BF16, 1024),      # head count without a factor of 8, one row past a tile
+    (1, 1000, 1, 64, False, I.BF16, 1000),      # a thousand single-key heads
+])
+def test_extreme_shapes_sampled(B, H, N, d, causal, dtype, nrows):
+    """Shapes at the ends of what the schedule has to deal out (very long heads, very many heads,
+    head counts that do not divide over the XCDs), compared on sampled rows; every output finite."""
+    w = I.Workload("extreme", B, H, N, d, causal, dtype)
+    qb, kb, vb = I.make_qkv(w, seed=N)
+    rows = I.sample_rows(w, nrows, seed=N)
+    O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, w.causal, w.scale, w.dtype, rows=rows)
+    print(f"case {w.label} default variant", flush=True)
+    O, l = run_gpu(qb, kb, vb, w.causal, w.scale, w.dtype)
+    check(O.reshape(-1, w.d)[rows], l.reshape(-1)[rows], O_ref, l_ref, w.dtype, what=w.label)
+    assert np.isfinite(O).all() and np.isfinite(l).all()
+
+
 @pytest.mark.parametrize("dtype", [I.F16, I.BF16])
 @pytest.mark.parametrize("kind", I.ADVERSARIAL)
 def test_adversarial_inputs(kind, dtype):
