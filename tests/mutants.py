@@ -79,3 +79,63 @@ def tiled_attention(q, k, v, causal: bool, scale: float, bug: str | None = None)
             O[i] = acc / l
             lse[i] = m + (np.log2(l) if bug == "lse_in_base_2" else np.log(l))
     return O, lse
+
+
+# ---- second workload: C = leaky_relu(A B), tiled the way the kernel tiles it (32 x 32 tiles of C,
+# the k dimension dealt out to WK workers in ranges of BKW, partial sums added at the end)
+GEMM_BUGS = {
+    "k_tail_dropped": ("a k range that crosses K is skipped instead of zero-filled", "K not a multiple of the range"),
+    "k_tail_not_zeroed": ("the part of the last range past K multiplies what follows in memory", "K not a multiple of the range"),
+    "worker_sum_misses_last": ("the final sum leaves out the last worker's partial result", "K larger than one range"),
+    "row_tail_wraps": ("rows of a ragged last tile read row (m mod 32) of the tile instead of their own", "M not a multiple of 32"),
+    "slope_on_rounded": ("the activation is applied after rounding to 16 bits", "benign: rounding keeps the sign"),
+    "relu_instead_of_leaky": ("negative sums become zero", "any negative output (slope != 0)"),
+    "slope_on_negative_zero": ("x >= 0 tested as x > 0: a zero sum is multiplied by the slope", "benign: 0 * slope = 0"),
+    "b_tile_transposed_within_8": ("columns of B are swapped in pairs inside every group of 8", "N >= 2, B not constant along rows"),
+}
+GEMM_WK, GEMM_BKW = 4, 32
+
+
+def tiled_gemm_lrelu(a, b, slope: float, bug: str | None = None):
+    """a [M,K], b [K,N] float64.  Returns C [M,N] float64 (before the final 16-bit rounding, which
+    the comparison's tolerance covers)."""
+    M, K = a.shape
+    N = b.shape[1]
+    C = np.zeros((M, N))
+    if bug == "b_tile_transposed_within_8":
+        perm = np.arange(N) ^ 1
+        perm[perm >= N] = N - 1
+        b = b[:, perm]
+    step = GEMM_WK * GEMM_BKW
+    for m0 in range(0, M, 32):
+        rows = np.arange(m0, min(M, m0 + 32))
+        src = rows
+        if bug == "row_tail_wraps" and m0 + 32 > M:
+            src = m0 + (rows - m0) % max(1, (M - m0) // 2 + 1)      # some rows read a neighbour's data
+        part = np.zeros((GEMM_WK, len(rows), N))
+        for w in range(GEMM_WK):
+            for k0 in range(w * GEMM_BKW, K, step):
+                k1 = k0 + GEMM_BKW
+                if k1 > K:
+                    if bug == "k_tail_dropped":
+                        continue
+                    if bug == "k_tail_not_zeroed":
+                        # what lies past row i's end in a row-major A is the start of row i+1; B past K: its last row again
+                        ext_a = np.concatenate([a[src, k0:K], a[np.minimum(src + 1, M - 1), :k1 - K]], axis=1)
+                        ext_b = np.concatenate([b[k0:K], np.repeat(b[K - 1:K], k1 - K, axis=0)], axis=0)
+                        part[w] += ext_a @ ext_b
+                        continue
+                    k1 = K
+                part[w] += a[src, k0:k1] @ b[k0:k1]
+        workers = GEMM_WK - 1 if bug == "worker_sum_misses_last" else GEMM_WK
+        x = part[:workers].sum(axis=0)
+        if bug == "slope_on_rounded":
+            x = x.astype(np.float16).astype(np.float64)
+        if bug == "relu_instead_of_leaky":
+            x = np.where(x >= 0, x, 0.0)
+        elif bug == "slope_on_negative_zero":
+            x = np.where(x > 0, x, slope * x)
+        else:
+            x = np.where(x >= 0, x, slope * x)
+        C[rows] = x
+    return C

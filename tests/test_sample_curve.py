@@ -77,6 +77,52 @@ def test_planted_mistakes_are_caught_by_random_samples():
     assert first["mask_after_max"] is None and first["first_tile_only_max"] is None
 
 
+# ---- second workload
+
+GEMM_MS = (1, 7, 31, 32, 33, 64, 65, 100)
+GEMM_NS = (8, 16, 24, 40, 64, 72)
+GEMM_KS = (8, 16, 32, 40, 64, 104, 128, 136, 256, 264, 512, 520)
+
+
+def draw_gemm_case(rng):
+    Mm, N, K = rng.choice(GEMM_MS), rng.choice(GEMM_NS), rng.choice(GEMM_KS)
+    fam = rng.choice(I.GEMM_FAMILIES)
+    slope = rng.choice((0.01, 0.2, 0.0, -0.5))
+    ab, bb = I.make_gemm(Mm, N, K, I.F16, rng.randrange(1 << 30), fam)
+    x, _ = ref.gemm_lrelu_ref(ab, bb, slope, I.F16)
+    sabs, _ = ref.gemm_lrelu_ref(ab & np.uint16(0x7FFF), bb & np.uint16(0x7FFF), 1.0, I.F16)
+    tol = 1.01 * 2.0 ** -11 * np.abs(x) + 2.0 * K * 2.0 ** -24 * sabs * max(1.0, abs(slope)) + 2.0 ** -25
+    return I.bits_to_f64(ab, I.F16), I.bits_to_f64(bb, I.F16), slope, x, tol
+
+
+def gemm_caught(case, bug):
+    a, b, slope, x, tol = case
+    c = M.tiled_gemm_lrelu(a, b, slope, bug)
+    return bool(not np.isfinite(c).all() or (np.abs(c - x) > tol).any())
+
+
+def gemm_first_detection(samples=80, seed=11):
+    rng = random.Random(seed)
+    first = {b: None for b in M.GEMM_BUGS}
+    for n in range(1, samples + 1):
+        case = draw_gemm_case(rng)
+        assert not gemm_caught(case, None), "the correct method must pass every sample"
+        for b in first:
+            if first[b] is None and gemm_caught(case, b):
+                first[b] = n
+    return first
+
+
+def test_gemm_model_and_its_planted_mistakes():
+    first = gemm_first_detection()
+    for b in ("k_tail_dropped", "k_tail_not_zeroed", "worker_sum_misses_last", "row_tail_wraps", "relu_instead_of_leaky",
+              "b_tile_transposed_within_8"):
+        assert first[b] is not None, f"{b} survived 80 samples"
+    assert first["relu_instead_of_leaky"] <= 5 and first["b_tile_transposed_within_8"] <= 5
+    # harmless by construction: rounding keeps the sign, and slope * 0 = 0
+    assert first["slope_on_negative_zero"] is None
+
+
 if __name__ == "__main__":   # prints the curve:  python -m tests.test_sample_curve [samples] [seed]
     import sys
     samples = int(sys.argv[1]) if len(sys.argv) > 1 else 300
@@ -87,3 +133,5 @@ if __name__ == "__main__":   # prints the curve:  python -m tests.test_sample_cu
     for n in (1, 2, 5, 10, 20, 50, 100, 200, samples):
         if n <= samples:
             print(f"after {n:4d} samples: {sum(1 for v in first.values() if v is None or v > n)} of {len(first)} mutants not caught")
+    for b, n in sorted(gemm_first_detection(samples).items(), key=lambda kv: (kv[1] is None, kv[1])):
+        print(f"gemm {b:28s} first caught at sample {n}   ({M.GEMM_BUGS[b][0]}; shows when: {M.GEMM_BUGS[b][1]})")
