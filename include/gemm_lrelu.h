@@ -60,7 +60,8 @@ int gemm_lrelu_time(const void* a, const void* b, void* c, int M, int N, int K, 
  * the kernel symbol in it; the kernel must take the arguments, launch shape and LDS of variant
  * `variant_id` for element type `dtype`.  Returns a handle >= 0 (at most 64 are open at a time;
  * GEMM_EINVAL when the table is full), or a negative error.  Unload only after the work that
- * uses the handle has finished. */
+ * uses the handle has finished.  The table of handles is process-wide and unguarded: load and
+ * unload from one thread at a time (launches may come from any thread). */
 int gemm_lrelu_codeobj_load(const char* path, const char* kernel_name, int variant_id, int dtype);
 int gemm_lrelu_codeobj_unload(int handle);
 /* gemm_lrelu / gemm_lrelu_time with the loaded kernel in place of the built-in one. */
