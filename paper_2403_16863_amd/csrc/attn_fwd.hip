@@ -17,17 +17,19 @@ typedef void (*KernelFn)(const Params);
 
 struct Variant {
     int bn, nw, qb, occ, ldp, pipe, pf, prio;  // knob values
-    int coords[7];                             // lattice coordinates (indices into the knob value lists)
+    int coords[8];                             // lattice coordinates (indices into the knob value lists)
     // kernels indexed [d == 128][dtype][causal]; null = not built for that combination
     KernelFn fn[2][2][2];
 };
 
 // Knob value lists (lattice axes): bn {32,64,128}  nw {4,8}  qb {1,2}  ldp {0,1}
-// pipe {0,1,2}  pf {2,4,6,8}  prio {0,1}.  The occupancy target follows from nw and qb (two
-// workgroups per CU when one holds four waves of one query block each) and is no axis.
-const char* const kKnobNames[] = {"bn", "nw", "qb", "ldp", "pipe", "pf", "prio"};
-const int kKnobSizes[] = {3, 2, 2, 2, 3, 4, 2};
-constexpr int kNumKnobs = 7;
+// pipe {0,1,2}  pf {2,4,6,8}  prio {0,1}  dense {0,1}.  The occupancy target follows from nw and
+// qb (two workgroups per CU when one holds four waves of one query block each); dense = 1 asks
+// for one workgroup more than that (three waves per SIMD: their vector instructions fill the
+// issue slots a single wave leaves empty; d = 64 only, where the registers allow it).
+const char* const kKnobNames[] = {"bn", "nw", "qb", "ldp", "pipe", "pf", "prio", "dense"};
+const int kKnobSizes[] = {3, 2, 2, 2, 3, 4, 2, 2};
+constexpr int kNumKnobs = 8;
 
 #define ATTN_KN(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO) attn::Knobs<BN, NW, QB, OCC, LDP, PIPE, PF, PRIO>
 #define ATTN_KERNELS_FOR(D, ...)                                                        \
@@ -44,20 +46,21 @@ constexpr int kNumKnobs = 7;
 #define IDX_NW(x) ((x) == 4 ? 0 : 1)
 #define IDX_QB(x) ((x) == 1 ? 0 : 1)
 #define IDX_PF(x) ((x) / 2 - 1)
+#define IDX_DENSE(NW, QB, OCC) ((OCC) - (((NW) == 4 && (QB) == 1) ? 2 : 1))
 
 #define VARIANT_BOTH(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)                                          \
     {BN, NW, QB, OCC, LDP, PIPE, PF, PRIO,                                                          \
-     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), LDP, PIPE, IDX_PF(PF), PRIO},               \
+     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), LDP, PIPE, IDX_PF(PF), PRIO, IDX_DENSE(NW, QB, OCC)},               \
      {ATTN_KERNELS_FOR(64, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO),                                   \
       ATTN_KERNELS_FOR(128, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)}}
 #define VARIANT_D64(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)                                           \
     {BN, NW, QB, OCC, LDP, PIPE, PF, PRIO,                                                          \
-     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), LDP, PIPE, IDX_PF(PF), PRIO},               \
+     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), LDP, PIPE, IDX_PF(PF), PRIO, IDX_DENSE(NW, QB, OCC)},               \
      {ATTN_KERNELS_FOR(64, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO), ATTN_NO_KERNELS}}
 
 #define VARIANT_D128(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)                                          \
     {BN, NW, QB, OCC, LDP, PIPE, PF, PRIO,                                                          \
-     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), LDP, PIPE, IDX_PF(PF), PRIO},               \
+     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), LDP, PIPE, IDX_PF(PF), PRIO, IDX_DENSE(NW, QB, OCC)},               \
      {ATTN_NO_KERNELS, ATTN_KERNELS_FOR(128, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)}}
 
 const Variant kVariants[] = {
@@ -78,6 +81,9 @@ const Variant kVariants[] = {
     VARIANT_D64(128, 4, 1, 2, 1, 0, 4, 0),
     VARIANT_D128(64, 8, 1, 1, 1, 2, 2, 1),   // 15, 16: MFMA work in both ping-pong clusters
     VARIANT_D128(64, 8, 1, 1, 1, 2, 4, 1),
+    VARIANT_D64(64, 4, 1, 3, 1, 0, 4, 0),    // 17 .. 19: three free-running workgroups per CU (d = 64)
+    VARIANT_D64(64, 4, 1, 3, 1, 0, 4, 1),
+    VARIANT_D64(64, 4, 1, 3, 1, 0, 2, 1),
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -332,7 +338,7 @@ int attn_variant_from_coords(const int* coords) {
 // sequences with head_dim 64; short sequences with head_dim 64 have too few such tiles to
 // go round and run the free-running order on 128-row tiles.  (Ids index kVariants.)
 constexpr int kDefaultD128 = 11;
-constexpr int kDefaultD64Long = 10;
+constexpr int kDefaultD64Long = 18;
 constexpr int kDefaultD64Short = 3;
 
 int attn_default_variant(int N, int d, int dtype, int causal) {
