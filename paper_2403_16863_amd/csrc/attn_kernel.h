@@ -131,13 +131,17 @@ __device__ __forceinline__ float xhalf_max(float x) {
 // the 256-byte line index so 16 consecutive rows land on 16 distinct bank groups.
 __device__ __forceinline__ int k_swz(int chunk) { return (chunk & ~15) | ((chunk ^ (chunk >> 4)) & 15); }
 // V is read with the transposing load: a 16-lane group touches 4 consecutive key
-// rows x 32 bytes.  32-byte slots are XOR-ed with a code of (row & 3) chosen so the
-// four rows of one read and both lane groups of a half-wave hit disjoint banks.
+// rows x 32 bytes, and the LDS serves two such groups (the two 16-column halves of a
+// 32-column block: two neighbouring 32-byte slots) per clock, 256 bytes wide.  32-byte
+// slots are XOR-ed with a code of (row & 3) chosen so that those 4 rows x 2 slots hit eight
+// different 32-byte bank groups: with 256-byte rows (d = 128) every row covers all groups and
+// the codes 0, 2, 5, 7 do it; with 128-byte rows (d = 64) rows r and r + 2 share their groups
+// and the codes 0, 0, 2, 2 do.
 template <int D>
 __device__ __forceinline__ int v_swz_slot(int row, int slot) {
     const int r = row & 3;
-    const int code = ((r << 1) & 6) | (r >> 1);  // 0,2,5,7
-    return slot ^ (D == 128 ? code : (code & 3));
+    const int code = D == 128 ? (((r << 1) & 6) | (r >> 1)) : (r & 2);
+    return slot ^ code;
 }
 
 // ---- work items and their schedule.  A work item is one query tile of one head; the grid
