@@ -70,16 +70,19 @@ struct Knobs {
     static constexpr int ROT = ROT_;  // 1: every workgroup of an XCD starts at another k (see the kernel)
 };
 
-// A piece in LDS: 32 rows of CPA 16-byte chunks, read row-wise (lane = row).  The chunk index is
-// XOR-ed with a code of the row so that 8 (and 16) consecutive rows reading the same logical
-// chunk spread evenly over the banks.  An involution: the same function maps both ways.
+// A piece in LDS: 32 rows of CPA 16-byte chunks, read row-wise (lane = row).  The LDS serves 16
+// lanes x 16 bytes = 256 bytes per clock, i.e. 16 / CPA whole rows of bank groups: the chunk index
+// is XOR-ed with (row / (16 / CPA)), so the 16 consecutive rows of one clock, all reading the
+// same logical chunk, land on 16 different bank groups.  An involution: the same function maps
+// both ways.
 template <int CPA>
 __device__ __forceinline__ int a_code(int row) {
-    return CPA == 8 ? (row & 7) : ((row >> 1) & 3);
+    return CPA == 8 ? ((row >> 1) & 7) : ((row >> 2) & 3);
 }
 // B piece in LDS: BKW rows (k) of 64 bytes (32 columns), read with the transposing load, which
-// touches 4 consecutive rows x 32 bytes per 16 lanes: the two 32-byte halves of a row swap on
-// rows 2, 3 (mod 4), so the four rows hit four different quarters of the banks.
+// touches 4 consecutive rows x 32 bytes per 16 lanes, two such groups (the two halves of the
+// rows) per clock: 256 contiguous bytes, conflict-free as they lie.  The halves of a row swap
+// on rows 2, 3 (mod 4), which keeps that true and costs nothing.
 __device__ __forceinline__ int b_code(int row) { return (row >> 1) & 1; }
 
 template <class T, class KN>
