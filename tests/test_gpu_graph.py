@@ -2,7 +2,6 @@
 synchronise, so a caller can record them into a graph.  A graph is replayed several times,
 with the program's own eager work and synchronisations in between, and every replay is compared
 with the eager result bit for bit."""
-import numpy as np
 import pytest
 
 from paper_2403_16863_amd import inputs as I

@@ -1,6 +1,5 @@
 """The schedule search on the GPU: admission against the oracle for every step's
 candidate, and the product's own admission test against the default variant."""
-import numpy as np
 import pytest
 
 from oracle import ref

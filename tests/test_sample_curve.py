@@ -5,7 +5,6 @@ the library's accuracy contract against the fp64 oracle."""
 import random
 
 import numpy as np
-import pytest
 
 from oracle import ref
 from paper_2403_16863_amd import inputs as I

@@ -1,5 +1,4 @@
 """Host logic of the strategy comparison and the knob attribution, on made-up timing tables."""
-import math
 import random
 
 from paper_2403_16863_amd import search_compare as SC

@@ -5,7 +5,6 @@ import os
 import random
 import re
 import shutil
-import subprocess
 import tempfile
 
 import pytest
