@@ -70,6 +70,7 @@ def test_benchmark_configs_sampled(idx, nrows):
     (64, 64, 64, 64, True, I.F16, 1024),        # 4096 heads of one tile each: more work items than workgroups
     (3, 37, 257, 128, True, I.BF16, 1024),      # head count without a factor of 8, one row past a tile
     (1, 1000, 1, 64, False, I.BF16, 1000),      # a thousand single-key heads
+    (2, 3, 4100, 64, True, I.BF16, 512),        # long causal d = 64 (three workgroups per CU), ragged tail
 ])
 def test_extreme_shapes_sampled(B, H, N, d, causal, dtype, nrows):
     """Shapes at the ends of what the schedule has to deal out (very long heads, very many heads,
