@@ -165,6 +165,20 @@ int attn_time_codeobj(int handle, const void* q, const void* k, const void* v, v
 int attn_mfma_ceiling(int random_operands, int iters, void* stream, unsigned long long* counters,
                       double* tflops, double* core_ghz);
 
+/* Measurement aid for the second ceiling of the path, the vector ALU (not part of the
+ * attention path).  Per score element the one-pass softmax issues one multiply-add, one exp2,
+ * one add and half a conversion to 16 bit; the kernel issues exactly that mix on register data
+ * (16 elements per round and lane, `iters` rounds) with `waves_per_simd` waves (1 to 4) on every
+ * SIMD, and reports the elements per second it sustained (*elements_per_s, host) and the core
+ * clock during the run (*core_ghz, host; 0 if the clock counters could not be read).  An
+ * element stands for 4*d floating-point operations of the two contractions, so
+ * 4 * d * elements_per_s is the rate the matrix cores would have to be fed at for the softmax
+ * not to be the bound.  counters: device memory, 3 x 8 bytes, written by the kernel
+ * (caller-owned).  Blocks until the kernel has finished.  ATTN_EINVAL on bad arguments,
+ * ATTN_ELAUNCH if a HIP call fails. */
+int attn_valu_ceiling(int waves_per_simd, int iters, void* stream, unsigned long long* counters,
+                      double* elements_per_s, double* core_ghz);
+
 /* Static text for an error code. */
 const char* attn_strerror(int code);
 

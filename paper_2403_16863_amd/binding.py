@@ -20,6 +20,7 @@ SYMBOLS = ("attn_fwd", "attn_fwd_variant", "attn_num_variants", "attn_variant_su
            "attn_variant_desc", "attn_num_knobs", "attn_knob_name", "attn_knob_size",
            "attn_variant_coords", "attn_variant_from_coords", "attn_default_variant",
            "attn_time_variant", "attn_strerror", "attn_schedule_grid", "attn_schedule_item", "attn_mfma_ceiling",
+           "attn_valu_ceiling",
            "attn_codeobj_load", "attn_codeobj_unload", "attn_fwd_codeobj", "attn_time_codeobj")
 
 _lib = None
@@ -82,6 +83,9 @@ def lib():
         L.attn_time_codeobj.argtypes = [i] + common + [i, i, ctypes.POINTER(ctypes.c_float)]
         L.attn_mfma_ceiling.restype = i
         L.attn_mfma_ceiling.argtypes = [i, i, ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+        L.attn_valu_ceiling.restype = i
+        L.attn_valu_ceiling.argtypes = [i, i, ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         L.attn_strerror.restype = ctypes.c_char_p
         L.attn_strerror.argtypes = [i]
@@ -272,6 +276,18 @@ def attn_mfma_ceiling(random_operands: bool, iters: int = 300000):
     if rc != 0:
         raise AttnError(rc, "attn_mfma_ceiling")
     return tf.value, ghz.value
+
+
+def attn_valu_ceiling(waves_per_simd: int, iters: int = 200000):
+    """(score elements per second, core clock in GHz) of the softmax's own instruction mix; see the header."""
+    import torch
+    counters = torch.zeros(3, dtype=torch.int64, device="cuda")
+    eps, ghz = ctypes.c_double(0), ctypes.c_double(0)
+    rc = lib().attn_valu_ceiling(int(waves_per_simd), int(iters), torch.cuda.current_stream().cuda_stream, counters.data_ptr(),
+                                 ctypes.byref(eps), ctypes.byref(ghz))
+    if rc != 0:
+        raise AttnError(rc, "attn_valu_ceiling")
+    return eps.value, ghz.value
 
 
 def attn_default_variant(N: int, d: int, dtype: int, causal: bool) -> int:

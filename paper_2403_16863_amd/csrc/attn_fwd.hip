@@ -16,22 +16,26 @@ using attn::Params;
 typedef void (*KernelFn)(const Params);
 
 struct Variant {
-    int bn, nw, qb, occ, ldp, pipe, pf, prio;  // knob values
-    int coords[8];                             // lattice coordinates (indices into the knob value lists)
+    int bn, nw, qb, occ, ldp, pipe, pf, prio, ilv, ldpos;  // knob values
+    int coords[10];                                     // lattice coordinates (indices into the knob value lists)
     // kernels indexed [d == 128][dtype][causal]; null = not built for that combination
     KernelFn fn[2][2][2];
 };
 
 // Knob value lists (lattice axes): bn {32,64,128}  nw {4,8}  qb {1,2}  ldp {0,1}
-// pipe {0,1,2}  pf {2,4,6,8}  prio {0,1}  dense {0,1}.  The occupancy target follows from nw and
-// qb (two workgroups per CU when one holds four waves of one query block each); dense = 1 asks
-// for one workgroup more than that (three waves per SIMD: their vector instructions fill the
-// issue slots a single wave leaves empty; d = 64 only, where the registers allow it).
-const char* const kKnobNames[] = {"bn", "nw", "qb", "ldp", "pipe", "pf", "prio", "dense"};
-const int kKnobSizes[] = {3, 2, 2, 2, 3, 4, 2, 2};
-constexpr int kNumKnobs = 8;
+// pipe {0,1,2,3}  pf {2,4,6,8}  prio {0,1,2}  dense {0,1}  ilv {0,1,2}  ldpos {0,1,2}.  The occupancy
+// target follows from nw and qb (two workgroups per CU when one holds four waves of one query block
+// each); dense = 1 asks for one workgroup more than that (three waves per SIMD: their vector
+// instructions fill the issue slots a single wave leaves empty; d = 64 only, where the registers
+// allow it).  ilv = how MFMA, LDS-read, transcendental and other vector instructions are grouped
+// in the interleaved order (sched_group_barrier patterns); ldpos = where in that order's stream a
+// wave issues its tile loads (all after the barrier, after fixed MFMA slots, after slots that
+// depend on the wave): the position of the memory instructions, which is what Sec. 3.1 perturbs.
+const char* const kKnobNames[] = {"bn", "nw", "qb", "ldp", "pipe", "pf", "prio", "dense", "ilv", "ldpos"};
+const int kKnobSizes[] = {3, 2, 2, 2, 4, 4, 3, 2, 3, 3};
+constexpr int kNumKnobs = 10;
 
-#define ATTN_KN(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO) attn::Knobs<BN, NW, QB, OCC, LDP, PIPE, PF, PRIO>
+#define ATTN_KN(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO, ILV, LDPOS) attn::Knobs<BN, NW, QB, OCC, LDP, PIPE, PF, PRIO, ILV, LDPOS>
 #define ATTN_KERNELS_FOR(D, ...)                                                        \
     {                                                                                   \
         {(KernelFn)attn::attn_fwd_kernel<attn::F16, D, false, ATTN_KN(__VA_ARGS__)>,      \
@@ -47,21 +51,25 @@ constexpr int kNumKnobs = 8;
 #define IDX_QB(x) ((x) == 1 ? 0 : 1)
 #define IDX_PF(x) ((x) / 2 - 1)
 #define IDX_DENSE(NW, QB, OCC) ((OCC) - (((NW) == 4 && (QB) == 1) ? 2 : 1))
+#define VARIANT_HEAD(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO, ILV, LDPOS)                              \
+    BN, NW, QB, OCC, LDP, PIPE, PF, PRIO, ILV, LDPOS,                                               \
+    {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), LDP, PIPE, IDX_PF(PF), PRIO, IDX_DENSE(NW, QB, OCC), ILV, LDPOS}
 
+// variants of the first three loop orders have no interleave pattern and no load position
 #define VARIANT_BOTH(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)                                          \
-    {BN, NW, QB, OCC, LDP, PIPE, PF, PRIO,                                                          \
-     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), LDP, PIPE, IDX_PF(PF), PRIO, IDX_DENSE(NW, QB, OCC)},               \
-     {ATTN_KERNELS_FOR(64, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO),                                   \
-      ATTN_KERNELS_FOR(128, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)}}
+    {VARIANT_HEAD(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO, 0, 0),                                      \
+     {ATTN_KERNELS_FOR(64, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO, 0, 0),                             \
+      ATTN_KERNELS_FOR(128, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO, 0, 0)}}
 #define VARIANT_D64(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)                                           \
-    {BN, NW, QB, OCC, LDP, PIPE, PF, PRIO,                                                          \
-     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), LDP, PIPE, IDX_PF(PF), PRIO, IDX_DENSE(NW, QB, OCC)},               \
-     {ATTN_KERNELS_FOR(64, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO), ATTN_NO_KERNELS}}
-
+    {VARIANT_HEAD(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO, 0, 0),                                      \
+     {ATTN_KERNELS_FOR(64, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO, 0, 0), ATTN_NO_KERNELS}}
 #define VARIANT_D128(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)                                          \
-    {BN, NW, QB, OCC, LDP, PIPE, PF, PRIO,                                                          \
-     {IDX_BN(BN), IDX_NW(NW), IDX_QB(QB), LDP, PIPE, IDX_PF(PF), PRIO, IDX_DENSE(NW, QB, OCC)},               \
-     {ATTN_NO_KERNELS, ATTN_KERNELS_FOR(128, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO)}}
+    {VARIANT_HEAD(BN, NW, QB, OCC, LDP, PIPE, PF, PRIO, 0, 0),                                      \
+     {ATTN_NO_KERNELS, ATTN_KERNELS_FOR(128, BN, NW, QB, OCC, LDP, PIPE, PF, PRIO, 0, 0)}}
+// the interleaved order (pipe 3), d = 128: 256-row query tiles, 64-key tiles
+#define VARIANT_ILV(LDP, PF, PRIO, ILV, LDPOS)                                                      \
+    {VARIANT_HEAD(64, 8, 1, 1, LDP, 3, PF, PRIO, ILV, LDPOS),                                       \
+     {ATTN_NO_KERNELS, ATTN_KERNELS_FOR(128, 64, 8, 1, 1, LDP, 3, PF, PRIO, ILV, LDPOS)}}
 
 const Variant kVariants[] = {
     VARIANT_BOTH(64, 4, 1, 2, 1, 0, 4, 0),   // 0: the hand-written default
@@ -84,6 +92,18 @@ const Variant kVariants[] = {
     VARIANT_D64(64, 4, 1, 3, 1, 0, 4, 0),    // 17 .. 19: three free-running workgroups per CU (d = 64)
     VARIANT_D64(64, 4, 1, 3, 1, 0, 4, 1),
     VARIANT_D64(64, 4, 1, 3, 1, 0, 2, 1),
+    VARIANT_BOTH(64, 8, 1, 1, 1, 1, 4, 2),   // 20: ping-pong, priority raised while a wave issues tile loads
+    VARIANT_ILV(0, 4, 0, 0, 0),              // 21 ..: the interleaved order, tiles through registers
+    VARIANT_ILV(0, 4, 0, 0, 1),
+    VARIANT_ILV(0, 4, 0, 0, 2),
+    VARIANT_ILV(0, 2, 0, 0, 1),
+    VARIANT_ILV(0, 8, 0, 0, 1),
+    VARIANT_ILV(0, 4, 1, 0, 1),
+    VARIANT_ILV(0, 4, 2, 0, 1),
+    VARIANT_ILV(0, 4, 0, 1, 1),
+    VARIANT_ILV(0, 4, 0, 2, 1),
+    VARIANT_ILV(1, 4, 0, 0, 0),              // 30, 31: the interleaved order, tiles straight to LDS
+    VARIANT_ILV(1, 4, 0, 0, 1),
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -277,6 +297,42 @@ __global__ __launch_bounds__(256) void mfma_ceiling_kernel(unsigned long long* c
     if (sum == 1.2345e-30f) counters[2] = 1;  // keeps the accumulators alive
 }
 
+// ---- measurement aid: what the vector ALU sustains on the softmax's own instruction mix.  Per
+// score element the one-pass softmax issues one fma (scale and shift), one exp2, one add (row sum)
+// and half a conversion (two probabilities per packed 16-bit pair); this kernel issues exactly
+// that mix on independent data from registers, 16 elements per round like one 32-key half tile,
+// with a chosen number of waves per SIMD.  Ordinary scalar float code: the build keeps the compiler
+// from forming packed-fp32 instructions.
+__global__ __launch_bounds__(256) void valu_ceiling_kernel(unsigned long long* counters, int iters, float scale, float shift) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    float x[16];
+    for (int i = 0; i < 16; ++i) x[i] = -0.01f * (float)((threadIdx.x * 16 + i) & 255);
+    float rs0 = 0.f, rs1 = 0.f;
+    unsigned keep = 0;
+    const unsigned long long c0 = clock64(), r0 = wall_clock64();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+            const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(x[i], scale, shift));
+            const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(x[i + 1], scale, shift));
+            rs0 += e0;
+            rs1 += e1;
+            unsigned pk = __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{e0, e1}, bf16x2));
+            asm volatile("" : "+v"(pk));  // the conversion is part of the mix: keep it
+            keep ^= pk;
+        }
+        asm volatile("" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]));
+        asm volatile("" : "+v"(x[8]), "+v"(x[9]), "+v"(x[10]), "+v"(x[11]), "+v"(x[12]), "+v"(x[13]), "+v"(x[14]), "+v"(x[15]));
+    }
+    const unsigned long long c1 = clock64(), r1 = wall_clock64();
+    if (blockIdx.x == 7 && threadIdx.x == 0) {
+        counters[0] = c1 - c0;  // core clock cycles
+        counters[1] = r1 - r0;  // ticks of the constant 100 MHz clock
+    }
+    if (rs0 + rs1 == 1.2345e-30f || keep == 0x12345678u) counters[2] = 1;  // keeps the results alive
+}
+
 }  // namespace
 
 extern "C" {
@@ -310,8 +366,8 @@ int attn_variant_supported(int variant_id, int d, int dtype, int causal) {
 int attn_variant_desc(int variant_id, char* buf, int buflen) {
     if (variant_id < 0 || variant_id >= kNumVariants || !buf || buflen < 1) return ATTN_EINVAL;
     const Variant& v = kVariants[variant_id];
-    return snprintf(buf, (size_t)buflen, "bm=%d bn=%d nw=%d qb=%d occ=%d ldp=%d pipe=%d pf=%d prio=%d",
-                    32 * v.qb * v.nw, v.bn, v.nw, v.qb, v.occ, v.ldp, v.pipe, v.pf, v.prio);
+    return snprintf(buf, (size_t)buflen, "bm=%d bn=%d nw=%d qb=%d occ=%d ldp=%d pipe=%d pf=%d prio=%d ilv=%d ldpos=%d",
+                    32 * v.qb * v.nw, v.bn, v.nw, v.qb, v.occ, v.ldp, v.pipe, v.pf, v.prio, v.ilv, v.ldpos);
 }
 
 int attn_num_knobs(void) { return kNumKnobs; }
@@ -443,6 +499,32 @@ int attn_mfma_ceiling(int random_operands, int iters, void* stream, unsigned lon
     hipEventDestroy(e1);
     if (rc != ATTN_OK) return rc;
     *tflops = (double)blocks * 4 * (double)iters * 4 * 32768.0 / ((double)ms * 1e-3) / 1e12;
+    *core_ghz = h[1] ? (double)h[0] / ((double)h[1] * 10.0) : 0.0;
+    return ATTN_OK;
+}
+
+int attn_valu_ceiling(int waves_per_simd, int iters, void* stream, unsigned long long* counters,
+                      double* elements_per_s, double* core_ghz) {
+    if (waves_per_simd < 1 || waves_per_simd > 4 || iters < 1 || !counters || !elements_per_s || !core_ghz) return ATTN_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const int blocks = waves_per_simd * cu_count();  // 256 threads: one wave on each SIMD of a CU
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return ATTN_ELAUNCH;
+    if (hipEventCreate(&e1) != hipSuccess) { hipEventDestroy(e0); return ATTN_ELAUNCH; }
+    int rc = ATTN_OK;
+    float ms = 0.f, scale = 0.127517f, shift = -0.25f;
+    unsigned long long h[2] = {0, 0};
+    void* args[] = {&counters, &iters, &scale, &shift};
+    if (hipEventRecord(e0, s) != hipSuccess ||
+        hipLaunchKernel((const void*)valu_ceiling_kernel, dim3(blocks), dim3(256), args, 0, s) != hipSuccess ||
+        hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+        hipEventElapsedTime(&ms, e0, e1) != hipSuccess ||
+        hipMemcpy(h, counters, sizeof h, hipMemcpyDeviceToHost) != hipSuccess)
+        rc = ATTN_ELAUNCH;
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    if (rc != ATTN_OK) return rc;
+    *elements_per_s = (double)blocks * 256.0 * (double)iters * 16.0 / ((double)ms * 1e-3);
     *core_ghz = h[1] ? (double)h[0] / ((double)h[1] * 10.0) : 0.0;
     return ATTN_OK;
 }

@@ -172,7 +172,7 @@ __host__ __device__ inline bool schedule_item(int G, int gidx, int BH, int nqt, 
 }
 
 // Schedule / shape knobs of one variant (the lattice the search walks).
-template <int BN_, int NW_, int QB_, int OCC_, int LDP_, int PIPE_, int PF_, int PRIO_>
+template <int BN_, int NW_, int QB_, int OCC_, int LDP_, int PIPE_, int PF_, int PRIO_, int ILV_ = 0, int LDPOS_ = 0>
 struct Knobs {
     static constexpr int BN = BN_;      // keys per K/V tile
     static constexpr int NW = NW_;      // waves per workgroup
@@ -181,14 +181,21 @@ struct Knobs {
     static constexpr int LDP = LDP_;    // K/V load path: 0 = through VGPRs, 1 = global -> LDS directly
     static constexpr int PIPE = PIPE_;  // 0 = per tile S, softmax, PV, waves run free;
                                         // 1 = two-cluster ping-pong between the two waves of a SIMD (MFMA | VALU),
-                                        // 2 = ping-pong with MFMA work in both clusters, softmax inside the PV MFMAs
+                                        // 2 = ping-pong with MFMA work in both clusters, softmax inside the PV MFMAs,
+                                        // 3 = one interleaved stream of MFMAs and softmax arithmetic per wave
     static constexpr int PF = PF_;      // LDS fragment prefetch distance of the MFMA streams, in MFMA steps
-    static constexpr int PRIO = PRIO_;  // 1 = raise the wave priority (s_setprio) while it runs an MFMA stream
+    static constexpr int PRIO = PRIO_;  // where the wave priority is raised (s_setprio): 0 = nowhere, 1 = while the wave runs an
+                                        // MFMA stream, 2 = while it issues tile loads (PIPE 1) / in the second wave of every SIMD (PIPE 3)
+    static constexpr int ILV = ILV_;    // PIPE 3: how MFMA, LDS-read and softmax instructions are grouped (see there)
+    static constexpr int LDPOS = LDPOS_;  // PIPE 3: where a wave issues its four tile loads of an iteration: 0 = all after the
+                                          // barrier, 1 = after MFMA slots 3, 11, 19, 27, 2 = after slots that depend on the wave
 };
 
 template <class T, int D, bool CAUSAL, class KN>
 __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Params p) {
     constexpr int BN = KN::BN, NW = KN::NW, QB = KN::QB, LDP = KN::LDP, PIPE = KN::PIPE, PF = KN::PF, PRIO = KN::PRIO;
+    constexpr int ILV = KN::ILV, LDPOS = KN::LDPOS;
+    constexpr int NB = 2;            // K buffers and V buffers in LDS
     constexpr int NT = NW * 64;
     constexpr int BM = 32 * QB * NW;
     constexpr int KS = D / 16;       // k-steps of the first contraction
@@ -203,7 +210,7 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
     constexpr int NVF = KT * 2 * DT;  // V fragments (MFMA steps of the second contraction) per tile
     constexpr int NKF = KS * KT;      // K fragments (MFMA steps of the first contraction) per tile
 
-    __shared__ __attribute__((aligned(256))) u32x4 smem[4 * TILE_CHUNKS];  // K0 V0 K1 V1
+    __shared__ __attribute__((aligned(256))) u32x4 smem[2 * NB * TILE_CHUNKS];  // K0 V0 K1 V1 (K2 V2)
     char* const smem_b = reinterpret_cast<char*>(smem);
 
     const int tid = threadIdx.x;
@@ -221,7 +228,11 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
         if (!item_of_round(round, bh, qt)) break;
         if (round > 0) __syncthreads();  // every wave is done with the previous item's tiles in LDS
         const int q0 = qt * BM;
-        const int qw0 = q0 + wave * (32 * QB);  // first query row of this wave
+        // Row block of this wave inside the query tile.  Waves w and w + NW/2 share a SIMD; under a
+        // causal mask the interleaved order (PIPE 3) gives them the blocks s and NW-1-s, so every SIMD
+        // gets the same number of visible keys on the diagonal tiles.
+        const int rblk = (PIPE == 3 && CAUSAL) ? (wave < NW / 2 ? wave : NW + NW / 2 - 1 - wave) : wave;
+        const int qw0 = q0 + rblk * (32 * QB);  // first query row of this wave
         const int qw_last = qw0 + 32 * QB - 1;  // causal: tile j is active for this wave iff j*BN <= qw_last
 
         const size_t head_off = (size_t)bh * N * D;
@@ -635,6 +646,313 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
                 step(c0, j);
                 if (j + 1 < nkt) step(c1, j + 1);
             }
+        } else if constexpr (PIPE == 3) {
+            // Interleaved order: every wave runs ONE instruction stream in which the MFMAs of two
+            // contractions and the softmax arithmetic of a third 32-key half tile alternate, so
+            // both waves of a SIMD always have matrix and vector work to issue (a wave that
+            // only issues MFMAs leaves about one pipe slot in six empty, a wave that only
+            // issues vector instructions gets one every 7 clocks against the port's 4.6).
+            // Work is cut into half tiles h = 0, 1, 2 ... of 32 keys:
+            //     QK(h): S_h = K_h Q^T          8 MFMAs, one accumulator
+            //     SM(h): P_h = exp2(..S_h..)     16 x (fma, exp2, add) + 8 conversions per lane
+            //     PV(h): O^T += V_h^T P_h^T      8 MFMAs, four accumulators
+            // and iteration j >= 1 of the tile loop (K tile j, V tile j-1 in LDS) runs
+            //     step a:  QK(2j)   -> sA | PV(2j-2) with pA | SM(2j-1): sB -> pB
+            //     step b:  QK(2j+1) -> sB | PV(2j-1) with pB | SM(2j):   sA -> pA
+            // 32 slots of one MFMA, its share of LDS reads (PF slots ahead) and one element of
+            // the softmax each.  Iteration 0 (S_0, S_1, P_0) is the prologue; a wave whose last
+            // visible tile is jl runs iterations 1 .. jl+1, the last one with QK on a tile it does
+            // not need (results dropped): one code path keeps the accumulators in place.  For the
+            // same reason there is one copy of the iteration, and the LDS buffers rotate through
+            // the per-lane read addresses (twelve additions per iteration) and the scalar load
+            // targets instead of through unrolled code.
+            // One workgroup barrier per tile: before it every wave has waited for its own share
+            // of K(j), V(j-1); after it the loads of K(j+1), V(j) go out into the buffers that
+            // were read in iteration j-1.
+            static_assert(NW == 8 && QB == 1 && BN == 64 && D == 128, "the interleaved order is written for 8 waves of 32 query rows, 64-key tiles and d = 128");
+            static_assert(32 % PF == 0, "the fragment ring must divide the 32 slots of an iteration");
+            const int jl = CAUSAL ? min(nkt - 1, qw_last / BN) : nkt - 1;  // last tile with a key this wave sees
+            f32x16 sA, sB;
+            u32x4 pA[2], pB[2];
+            const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+            auto mask_half = [&](f32x16& sh, int k0h) __attribute__((always_inline)) {
+                const bool need_mask = (k0h + 32 > N) || (CAUSAL && (k0h + 31 > qw0));
+                if (need_mask) {
+                    const int qi = qw0 + c;
+                    const int lim = CAUSAL ? min(qi, N - 1) : N - 1;  // last visible key
+                    const int rel = lim - k0h - 4 * g;               // register v holds key k0h + 8*(v/4) + 4*g + v%4
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        if (8 * (v >> 2) + (v & 3) > rel) sh[v] = -INFINITY;
+                }
+            };
+            auto exp_pack_half = [&](const f32x16& sh, u32x4(&ph)[2], float& rs) __attribute__((always_inline)) {
+                const float mb = m_use[0] * p.scale_l2;
+                float rs0 = 0.f, rs1 = 0.f;
+                static_for<2>([&](auto t_c) __attribute__((always_inline)) {
+                    constexpr int t = decltype(t_c)::value;
+                    u32x4 w;
+                    static_for<4>([&](auto h_c) __attribute__((always_inline)) {
+                        constexpr int h = decltype(h_c)::value;
+                        const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sh[8 * t + 2 * h], p.scale_l2, -mb));
+                        const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sh[8 * t + 2 * h + 1], p.scale_l2, -mb));
+                        w[h] = T::pack2(e0, e1);
+                        rs0 += e0;
+                        rs1 += e1;
+                    });
+                    ph[t] = w;
+                });
+                rs = rs0 + rs1;
+            };
+            auto raise_reference_half = [&](const f32x16& sh) __attribute__((always_inline)) {
+                float mx = sh[0];
+#pragma unroll
+                for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sh[v]);
+                const float m_new = fmaxf(m_use[0], xhalf_max(mx));
+                // finite from half tile 0 on: key 0 is visible to every query
+                const float alpha = __builtin_amdgcn_exp2f((m_use[0] - m_new) * p.scale_l2);
+                m_use[0] = m_new;
+                l_run[0] *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) o[0][dt][v] *= alpha;
+            };
+
+            // Tile movement of this order: buffer loads straight into LDS.  The buffer descriptor
+            // covers the head's N rows, the tile and piece go into the scalar offset, the lane's
+            // share (with the swizzle) is the one vector offset kept for the whole kernel.  Rows
+            // past the end of the sequence, and whole tiles past it, arrive as zeros (the range
+            // check of the buffer descriptor), so ragged tails need neither a branch nor a clamp;
+            // their scores are masked.  which = 0: K, 1: V; piece = 0, 1 (NT chunks each).
+            static_assert(LD_PER_THREAD == 2, "two pieces per tile and lane");
+            const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(Kh), 0, N * RB, 0x00020000);
+            const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(Vh), 0, N * RB, 0x00020000);
+            auto tile_load = [&](int which, int tile, int buf, int piece) __attribute__((always_inline)) {
+                constexpr int ROWS_PER_PIECE = NT / CPR;
+                char* dst = smem_b + buf * 2 * TILE_BYTES + which * TILE_BYTES + (piece * NT + wave * 64) * 16;
+                const unsigned soff = (unsigned)tile * (BN * RB) + piece * (ROWS_PER_PIECE * RB);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(which ? v_rsrc : k_rsrc, (lds_void_ptr)dst, 16, which ? goffV0 : goffK0, soff, 0, 0);
+            };
+            // The same piece through registers (LDP = 0): a wave's LDS reads queue behind its own loads
+            // to LDS that are still in flight, which stalls a stream that reads LDS all the time; a
+            // load into registers does not, and the piece is written to LDS when the stream is over.
+            auto tile_load_reg = [&](int which, int tile, int piece) __attribute__((always_inline)) -> u32x4 {
+                constexpr int ROWS_PER_PIECE = NT / CPR;
+                const unsigned soff = (unsigned)tile * (BN * RB) + piece * (ROWS_PER_PIECE * RB);
+                return __builtin_amdgcn_raw_buffer_load_b128(which ? v_rsrc : k_rsrc, which ? goffV0 : goffK0, soff, 0);
+            };
+            auto tile_store_reg = [&](int which, int buf, int piece, u32x4 val) __attribute__((always_inline)) {
+                *reinterpret_cast<u32x4*>(smem_b + buf * 2 * TILE_BYTES + which * TILE_BYTES + (piece * NT + tid) * 16) = val;
+            };
+
+            // Per-lane LDS read addresses of the tiles the current iteration reads (K tile j in
+            // buffer j % NB, V tile j-1 in buffer (j-1) % NB), advanced once per iteration.
+            int kaddr[KS], vaddr[DT];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) kaddr[ks] = (int)lds_address(smem_b) + koff[ks];
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) vaddr[dt] = (int)lds_address(smem_b) + TILE_BYTES + voff[dt];
+            // LDS fragment of slot i (0 .. 31) of an iteration: slots 0..15 are step a (first halves of
+            // both tiles), 16..31 step b; inside a step even slots are QK k-steps, odd slots PV
+            // steps (t, dt) = ((i/2)/4, (i/2)%4).
+            auto read_frag = [&](int i) __attribute__((always_inline)) -> u32x4 {
+                const int half = i >> 4, si = i & 15;
+                if (si & 1) {
+                    const int idx = si >> 1, t = idx >> 2, dt = idx & 3;
+                    const unsigned a = (unsigned)vaddr[dt] + (half * 32 + 16 * t) * RB;
+                    const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(unsigned long)a));
+                    const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(unsigned long)(a + 8 * RB)));
+                    return u32x4{lo[0], lo[1], hi[0], hi[1]};
+                } else {
+                    typedef const u32x4 __attribute__((address_space(3))) * lds_u32x4_ptr;
+                    return *(lds_u32x4_ptr)(unsigned long)((unsigned)kaddr[si >> 1] + half * 32 * RB);
+                }
+            };
+            // Fence between instruction groups.  ILV picks the group: 0 = one slot (an MFMA, then its
+            // LDS reads, then the softmax element), 1 = two slots, 2 = four slots; inside a
+            // group the order MFMA, LDS reads, transcendental, other vector work is requested
+            // from the scheduler with sched_group_barrier.
+            auto slot_fence = [&](int si) __attribute__((always_inline)) {
+                constexpr int G = ILV == 0 ? 1 : (ILV == 1 ? 2 : 4);
+                if ((si + 1) % G == 0) {
+                    if constexpr (ILV != 0) {
+#pragma unroll
+                        for (int r = 0; r < G; ++r) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // LDS reads
+                            __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);  // transcendental
+                            __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);  // other vector instructions
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+
+            u32x4 ring[PF];
+            // One step of 16 slots: QK of a half tile into sN (overwritten), PV with pO, softmax of
+            // sC into pN.  k0C = first key of the half tile sC belongs to; act = that half tile
+            // exists for this wave (false only for the dropped work of the last iteration).
+            auto half_step = [&](auto half_c, f32x16& sN, f32x16& sC, const u32x4(&pO)[2], u32x4(&pN)[2], int k0C, bool act,
+                                 auto&& after_mfma) __attribute__((always_inline)) {
+                constexpr int HALF = decltype(half_c)::value;
+                mask_half(sC, k0C);
+                const float mb = m_use[0] * p.scale_l2;
+                float rs0 = 0.f, rs1 = 0.f;
+                // two-stage software pipeline over the elements: slot si forms the exponential of
+                // element si+1 and sums / converts element si
+                float e_cur = __builtin_amdgcn_exp2f(__builtin_fmaf(sC[0], p.scale_l2, -mb));
+                float e_prev = 0.f;
+                u32x4 w;
+                static_for<16>([&](auto si_c) __attribute__((always_inline)) {
+                    constexpr int si = decltype(si_c)::value, i = HALF * 16 + si;
+                    if constexpr ((si & 1) == 0) {
+                        constexpr int ks = si >> 1;
+                        if constexpr (ks == 0) sN = T::mfma(ring[i % PF], qreg[0][ks], zero16);
+                        else sN = T::mfma(ring[i % PF], qreg[0][ks], sN);
+                    } else {
+                        constexpr int idx = si >> 1, t = idx >> 2, dt = idx & 3;
+                        o[0][dt] = T::mfma(ring[i % PF], pO[t], o[0][dt]);
+                    }
+                    after_mfma(std::integral_constant<int, i>{});
+                    if constexpr (i + PF < 32) ring[i % PF] = read_frag(i + PF);
+                    float e_next = 0.f;
+                    if constexpr (si + 1 < 16) e_next = __builtin_amdgcn_exp2f(__builtin_fmaf(sC[si + 1], p.scale_l2, -mb));
+                    if constexpr (si & 1) {
+                        rs1 += e_cur;
+                        unsigned packed = T::pack2(e_prev, e_cur);
+                        // pinned here: the slow path below overwrites P, so the compiler would otherwise
+                        // sink the conversions into the fast path and keep every exponential alive
+                        asm volatile("" : "+v"(packed));
+                        w[(si & 7) >> 1] = packed;
+                        if constexpr ((si & 7) == 7) pN[si >> 3] = w;
+                    } else {
+                        rs0 += e_cur;
+                    }
+                    e_prev = e_cur;
+                    e_cur = e_next;
+                    slot_fence(si);
+                });
+                // The row sum is consumed unconditionally (select, not branch): otherwise the
+                // compiler sinks the additions into the branch and keeps every exponential alive.
+                float rs = rs0 + rs1;
+                const bool bad = !(rs <= 256.0f);                       // true for inf and NaN too
+                if (__builtin_amdgcn_ballot_w64(bad && act) != 0) {  // wave-uniform, rare
+                    raise_reference_half(sC);
+                    exp_pack_half(sC, pN, rs);
+                }
+                l_run[0] += act ? rs : 0.f;
+            };
+
+            // ---- iteration 0: the first tiles, S_0 and S_1, P_0
+#pragma unroll
+            for (int piece = 0; piece < 2; ++piece) tile_load(0, 0, 0, piece);
+#pragma unroll
+            for (int piece = 0; piece < 2; ++piece) tile_load(1, 0, 0, piece);
+#pragma unroll
+            for (int piece = 0; piece < 2; ++piece) tile_load(0, 1, 1, piece);
+            load_q();
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            {
+                u32x4 kf[2];
+                kf[0] = *reinterpret_cast<const u32x4*>(smem_b + koff[0]);
+                kf[1] = *reinterpret_cast<const u32x4*>(smem_b + 32 * RB + koff[0]);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    u32x4 a0 = kf[0], a1 = kf[1];
+                    if (ks + 1 < KS) {
+                        kf[0] = *reinterpret_cast<const u32x4*>(smem_b + koff[ks + 1]);
+                        kf[1] = *reinterpret_cast<const u32x4*>(smem_b + 32 * RB + koff[ks + 1]);
+                    }
+                    sA = T::mfma(a0, qreg[0][ks], ks == 0 ? zero16 : sA);
+                    sB = T::mfma(a1, qreg[0][ks], ks == 0 ? zero16 : sB);
+                }
+                mask_half(sA, 0);
+                raise_reference_half(sA);
+                float rs;
+                exp_pack_half(sA, pA, rs);
+                l_run[0] += rs;
+            }
+
+            // ---- iterations 1 .. nkt.  kb / vb: buffers read in iteration j; kn: buffer K(j+1) goes to
+            // (V(j) goes to the buffer with K(j)'s index).  A wave runs the stream in iterations
+            // 1 .. jl+1 and only moves its share of the tiles in the others; these are two loops,
+            // because a branch around the stream makes the register allocator copy all accumulators
+            // on every trip.  Both loops together pass the same number of barriers in every wave.
+            int kb = 1 % NB, vb = 0;
+            u32x4 stg[LDP == 0 ? 4 : 1];
+            // load l of iteration j: 0, 1 = the pieces of K(j+1) (into buffer kn), 2, 3 = the pieces of V(j)
+            // (into the buffer with K(j)'s index)
+            auto load_number = [&](int j, int l, int kn) __attribute__((always_inline)) {
+                if constexpr (LDP == 1) {
+                    if (l < 2) tile_load(0, j + 1, kn, l & 1);
+                    else tile_load(1, j, kb, l & 1);
+                } else {
+                    stg[l] = tile_load_reg(l >> 1, l < 2 ? j + 1 : j, l & 1);
+                }
+            };
+            auto land_staged = [&](int kn) __attribute__((always_inline)) {  // LDP = 0: registers -> LDS, before the next barrier
+                if constexpr (LDP == 0) {
+#pragma unroll
+                    for (int l = 0; l < 4; ++l) tile_store_reg(l >> 1, l < 2 ? kn : kb, l & 1, stg[l]);
+                }
+            };
+            const int jrun = jl + 1;
+            for (int j = 1; j <= jrun; ++j) {
+                const int kn = kb + 1 == NB ? 0 : kb + 1;
+                // advance the read addresses: K from tile j-1's buffer to tile j's, V from tile j-2's to tile j-1's
+                {
+                    const int kstep = kb == 0 ? -(NB - 1) * 2 * TILE_BYTES : 2 * TILE_BYTES;
+                    const int vstep = j == 1 ? 0 : (vb == 0 ? -(NB - 1) * 2 * TILE_BYTES : 2 * TILE_BYTES);
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) kaddr[ks] += kstep;
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt) vaddr[dt] += vstep;
+                }
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's share of K(j), V(j-1) has landed
+                __syncthreads();
+                // This iteration's loads: K(j+1) and V(j), two 16-byte pieces per lane each, into
+                // buffers nobody reads in this iteration.  LDPOS = 0: all four right after the
+                // barrier.  LDPOS > 0: between the MFMAs of the stream (a load holds the issuing wave
+                // until the texture path has taken it, and eight waves issuing four loads each right
+                // after the barrier queue behind each other).
+                if constexpr (LDPOS == 0) {
+#pragma unroll
+                    for (int l = 0; l < 4; ++l) load_number(j, l, kn);
+                }
+                auto stream_load = [&](auto i_c) __attribute__((always_inline)) {
+                    constexpr int i = decltype(i_c)::value;
+                    // load l goes out after slot 8*l + 3 (LDPOS 1) or 8*l + wave (LDPOS 2: one wave per slot)
+                    if constexpr (LDPOS == 1) {
+                        if constexpr ((i & 7) == 3) load_number(j, i >> 3, kn);
+                    } else if constexpr (LDPOS == 2) {
+                        if ((i & 7) == wave) load_number(j, i >> 3, kn);
+                    }
+                };
+                if constexpr (PRIO == 1) __builtin_amdgcn_s_setprio(1);
+                if constexpr (PRIO == 2) { if (wave >= NW / 2) __builtin_amdgcn_s_setprio(1); }
+#pragma unroll
+                for (int i = 0; i < PF; ++i) ring[i] = read_frag(i);
+                __builtin_amdgcn_sched_barrier(0);
+                half_step(c0, sA, sB, pA, pB, (2 * j - 1) * 32, true, stream_load);
+                half_step(c1, sB, sA, pB, pA, 2 * j * 32, j <= jl, stream_load);
+                if constexpr (PRIO != 0) __builtin_amdgcn_s_setprio(0);
+                land_staged(kn);
+                vb = kb;
+                kb = kn;
+            }
+            for (int j = jrun + 1; j <= nkt; ++j) {
+                const int kn = kb + 1 == NB ? 0 : kb + 1;
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+#pragma unroll
+                for (int l = 0; l < 4; ++l) load_number(j, l, kn);
+                land_staged(kn);
+                vb = kb;
+                kb = kn;
+            }
         } else {
             // Ping-pong order for two waves per SIMD.  The tile loop is cut into two clusters:
             //     M_j : O += P(j) V(j)  and  S(j+1) = K(j+1) Q^T      (MFMA + LDS reads only)
@@ -686,7 +1004,9 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
                 // Every wave issues its share of a tile at the start of one of its V clusters
                 // (group B in slot 2j, group A in slot 2j+1).
                 auto slot_loads = [&](int j) __attribute__((always_inline)) {  // the loads of slot 2j; buffer indices are runtime here
+                    if constexpr (PRIO == 2) __builtin_amdgcn_s_setprio(2);
                     issue_tiles(j + 2, j & 1, j + 1, (j + 1) & 1);
+                    if constexpr (PRIO == 2) __builtin_amdgcn_s_setprio(0);
                 };
                 auto cluster_v = [&](int j) __attribute__((always_inline)) {
                     if (tile_active(j + 1)) softmax_tile(s, pk, (j + 1) * BN);
