@@ -133,33 +133,35 @@ def settle(A, w, tensors, variant, gpu_seconds=SETTLE_GPU_SECONDS):
 
 
 def time_steps(A, w, tensors, variant, warmup, steps, sample_device=False):
-    """Wall clock over exactly `steps` launches bracketed by synchronize, plus every launch's
-    duration from HIP events recorded on the launch stream between the launches."""
+    """Wall clock over exactly `steps` launches bracketed by synchronize, and the average launch
+    duration from one pair of HIP events recorded on the launch stream around the same launches.
+    Afterwards, outside the timed region, up to 50 more launches are bracketed one by one (an
+    event between every two launches adds a few microseconds each) for the median and minimum."""
     import numpy as np
     import torch
     q, k, v, out, lse = tensors
     stream = torch.cuda.current_stream()
     for _ in range(warmup):
         A.attn_fwd_variant(q, k, v, out, lse, w.causal, w.scale, variant)
-    events = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     sampler = DeviceSampler() if sample_device else None
     torch.cuda.synchronize()
     if sampler:
         sampler.start()
     t0 = time.perf_counter()
-    events[0].record(stream)
-    for i in range(steps):
+    e0.record(stream)
+    for _ in range(steps):
         A.attn_fwd_variant(q, k, v, out, lse, w.causal, w.scale, variant)
-        events[i + 1].record(stream)
+    e1.record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     if sampler:
         sampler.stop_flag.set()
         sampler.join()
-    per_launch = np.array([events[i].elapsed_time(events[i + 1]) for i in range(steps)]) * 1e-3
-    return {"wall_s": (t1 - t0) / steps, "evt_s": float(per_launch.mean()),
-            "launch_ms": {"mean": float(per_launch.mean() * 1e3), "median": float(np.median(per_launch) * 1e3),
-                          "min": float(per_launch.min() * 1e3), "max": float(per_launch.max() * 1e3)},
+    per_launch = np.array(A.attn_time_variant(q, k, v, out, lse, w.causal, w.scale, variant, 0, min(steps, 50)))
+    return {"wall_s": (t1 - t0) / steps, "evt_s": e0.elapsed_time(e1) * 1e-3 / steps,
+            "launch_ms": {"median": float(np.median(per_launch)), "min": float(per_launch.min()), "max": float(per_launch.max()),
+                          "launches": int(len(per_launch)), "note": "each launch between its own pair of events, after the timed region"},
             "device": sampler.result() if sampler else None}
 
 
@@ -223,6 +225,13 @@ def ceilings(A, achieved):
             "random_operands": {"TFLOP/s": tf_r, "core_GHz": ghz_r},
             "frac_of_random_operand_rate": achieved / tf_r if tf_r > 0 else None,
             "note": "bf16 MFMAs from registers only; with random operands the device lowers its clock"}
+    mix = {"note": "the tile loop's own instruction mix and nothing else (random operands, two waves per SIMD, "
+                   "no tile loads, barriers, masks or item boundaries): the ceiling of the loop body at this device's power limit"}
+    for mode, name in ((0, "mfma_only"), (1, "mfma_and_lds_reads"), (2, "mfma_lds_reads_and_softmax_arithmetic")):
+        tf, ghz = A.attn_mix_ceiling(mode)
+        mix[name] = {"TFLOP/s": tf, "core_GHz": ghz}
+    mix["frac_of_full_mix_rate"] = achieved / mix["mfma_lds_reads_and_softmax_arithmetic"]["TFLOP/s"]
+    mfma["loop_body_mix_kernel"] = mix
     valu = {"mix": "per score element 1 fma + 1 exp2 + 1 add + 1/2 conversion to 16 bit, from registers, no packed fp32",
             "note": "an element stands for 4*d flops of the two contractions: implied ceilings below"}
     for wps in (1, 2, 3):

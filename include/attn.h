@@ -18,13 +18,15 @@
  *
  * The schedule-variant entry points are the analogue of the paper's search
  * space (Sec. 3.1): a variant is one compile-time instruction schedule of the
- * same kernel (tile shape, LDS prefetch distance, instruction-group
- * interleaving, wave priority placement).  All variants compute the same
- * function.
+ * same kernel (tile shape, loop order, LDS prefetch distance, instruction-group
+ * interleaving, position of the tile loads, wave priority placement, load path,
+ * occupancy; attn_knob_name lists them).  All variants compute the same function.
  *
  * General rules
  *  - every pointer named "device" is a HIP device pointer owned by the caller;
- *    the library allocates nothing, frees nothing and keeps no mutable state;
+ *    the library allocates no device memory and frees none.  Its only mutable state
+ *    is process-wide and small: the compute-unit count of each device, read once,
+ *    and the table of loaded code objects (attn_codeobj_*), which is not synchronised;
  *  - calls are asynchronous: work is enqueued on `stream` (a hipStream_t passed
  *    as void*, NULL = the default stream) and the call returns without waiting;
  *  - the return value is ATTN_OK or a negative error code; on error nothing has
@@ -58,11 +60,24 @@ enum {
  *            overlap q, k or v.  Every element is written.
  *  lse     : device, [B,H,N] fp32, 4-byte aligned: natural-log log-sum-exp of the
  *            scaled scores over the visible keys.  Every element is written.
- *  B,H,N   : >= 1, any N (ragged last tiles are masked); B*H <= 65535*... see
- *            ATTN_EUNSUPPORTED.
+ *  B,H,N   : >= 1, any N (ragged last tiles are masked).  Limits, reported as
+ *            ATTN_EUNSUPPORTED: B*H*N*d <= 2^40 elements, and B*H*ceil(N/bm) <= 2^31-1
+ *            work items (bm = the variant's query tile, 128 or 256 rows).
  *  d       : 64 or 128.
  *  causal  : 0 = every key visible, otherwise key j is visible to query i iff j <= i.
  *  scale   : finite; multiplies q.k before the softmax (callers pass 1/sqrt(d)).
+ *
+ * Accuracy (fp32 accumulation, P rounded to `dtype` before the second contraction, O rounded
+ * once): with u = 2^-11 (binary16) or 2^-8 (bfloat16), the half-unit roundoff of `dtype`,
+ *     |O[c] - exact| <= u * |O[c]|  +  u * sum_j p_j |V[j,c]|  +  small fp32 terms,
+ * i.e. at most about 2 u max_j |V[j,c]|: 1e-3 * Vmax for binary16, 8e-3 * Vmax for bfloat16.
+ * The absolute bounds 1e-2 / 3e-2 that the tests use therefore hold for |V| below about 10
+ * (binary16) and 3.8 (bfloat16) in the worst case (a row that puts all its weight on large
+ * values of one sign); for larger outputs the bound is the relative one.
+ * lse is accurate to about 1e-6 relative (fp32 sums of unrounded probabilities).
+ * V magnitude: the one-pass method keeps the un-normalised sum of p*v in fp32, with p up to
+ * 2^8 before the reference maximum is raised, so |V| * N * 2^8 must stay below the fp32 range
+ * (3.4e38): every finite binary16 V qualifies, bfloat16 V must stay below about 1e38 / (256 N).
  *  dtype   : ATTN_F16 or ATTN_BF16.
  *  stream  : hipStream_t as void*, NULL = default stream.
  */
@@ -119,7 +134,10 @@ int attn_variant_from_coords(const int* coords);
 int attn_schedule_grid(int variant_id, int compute_units, int B, int H, int N);
 int attn_schedule_item(int grid, int workgroup, int BH, int nqt, int round, int* bh, int* qt);
 
-/* The variant attn_fwd uses for this shape. */
+/* The variant attn_fwd uses for this shape: the best admitted variant of the stored searches
+ * on MI355X (Sec. 4.1: candidates are ranked offline and the best one is deployed, at no
+ * run-time cost).  The choice depends on d and N only; dtype and causal are accepted so that a
+ * later ranking may use them, and are ignored today. */
 int attn_default_variant(int N, int d, int dtype, int causal);
 
 /* Feedback measurement of Sec. 3.3: `warmup` untimed launches, then `iters`
@@ -164,6 +182,20 @@ int attn_time_codeobj(int handle, const void* q, const void* k, const void* v, v
  * if a HIP call fails. */
 int attn_mfma_ceiling(int random_operands, int iters, void* stream, unsigned long long* counters,
                       double* tflops, double* core_ghz);
+
+/* Measurement aid: the ceiling of the tile loop's own instruction mix on this device (not part
+ * of the attention path).  Per 32x32x16 MFMA the loop reads one 1 KB operand fragment from LDS and
+ * issues one multiply-add, one exp2, one add and half a conversion to 16 bit per lane for the
+ * softmax.  The kernel issues that and nothing else (random operands, fragments read four steps
+ * ahead, two waves per SIMD, `iters` rounds of 16 MFMAs per wave; no tile loads, barriers, masks
+ * or item boundaries): mode 0 = MFMAs only, 1 = MFMAs and LDS reads, 2 = the whole mix.  The
+ * device runs it at its power limit, as it runs the attention kernel, so *tflops (host) is what
+ * the loop body can reach there; *core_ghz (host) is the clock during the run (0 if the clock
+ * counters could not be read).  counters: device memory, 3 x 8 bytes, written by the kernel
+ * (caller-owned).  Blocks until the kernel has finished.  ATTN_EINVAL on bad arguments,
+ * ATTN_ELAUNCH if a HIP call fails. */
+int attn_mix_ceiling(int mode, int iters, void* stream, unsigned long long* counters,
+                     double* tflops, double* core_ghz);
 
 /* Measurement aid for the second ceiling of the path, the vector ALU (not part of the
  * attention path).  Per score element the one-pass softmax issues one multiply-add, one exp2,

@@ -20,7 +20,7 @@ SYMBOLS = ("attn_fwd", "attn_fwd_variant", "attn_num_variants", "attn_variant_su
            "attn_variant_desc", "attn_num_knobs", "attn_knob_name", "attn_knob_size",
            "attn_variant_coords", "attn_variant_from_coords", "attn_default_variant",
            "attn_time_variant", "attn_strerror", "attn_schedule_grid", "attn_schedule_item", "attn_mfma_ceiling",
-           "attn_valu_ceiling",
+           "attn_valu_ceiling", "attn_mix_ceiling",
            "attn_codeobj_load", "attn_codeobj_unload", "attn_fwd_codeobj", "attn_time_codeobj")
 
 _lib = None
@@ -84,6 +84,9 @@ def lib():
         L.attn_mfma_ceiling.restype = i
         L.attn_mfma_ceiling.argtypes = [i, i, ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+        L.attn_mix_ceiling.restype = i
+        L.attn_mix_ceiling.argtypes = [i, i, ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         L.attn_valu_ceiling.restype = i
         L.attn_valu_ceiling.argtypes = [i, i, ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -275,6 +278,18 @@ def attn_mfma_ceiling(random_operands: bool, iters: int = 300000):
                                  ctypes.byref(tf), ctypes.byref(ghz))
     if rc != 0:
         raise AttnError(rc, "attn_mfma_ceiling")
+    return tf.value, ghz.value
+
+
+def attn_mix_ceiling(mode: int, iters: int = 20000):
+    """(TFLOP/s, core clock in GHz) of the tile loop's own instruction mix; see the header."""
+    import torch
+    counters = torch.zeros(3, dtype=torch.int64, device="cuda")
+    tf, ghz = ctypes.c_double(0), ctypes.c_double(0)
+    rc = lib().attn_mix_ceiling(int(mode), int(iters), torch.cuda.current_stream().cuda_stream, counters.data_ptr(),
+                                ctypes.byref(tf), ctypes.byref(ghz))
+    if rc != 0:
+        raise AttnError(rc, "attn_mix_ceiling")
     return tf.value, ghz.value
 
 

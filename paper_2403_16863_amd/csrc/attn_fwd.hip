@@ -176,6 +176,8 @@ int launch(const void* q, const void* k, const void* v, void* out, float* lse, i
     const long long nqt = ((long long)N + bm - 1) / bm;
     const long long total = nqt * B * H;
     if (total > 0x7fffffffLL) return ATTN_EUNSUPPORTED;
+    // the interleaved order addresses K and V of a head through a buffer descriptor: 32-bit byte offsets
+    if (var.pipe == 3 && (long long)N * d * 2 > 0xffffffffLL) return ATTN_EUNSUPPORTED;
 
     Params p;
     p.q = (const uint16_t*)q;
@@ -295,6 +297,77 @@ __global__ __launch_bounds__(256) void mfma_ceiling_kernel(unsigned long long* c
         counters[1] = r1 - r0;  // ticks of the constant 100 MHz clock
     }
     if (sum == 1.2345e-30f) counters[2] = 1;  // keeps the accumulators alive
+}
+
+// ---- measurement aid: what a kernel with this path's instruction mix sustains.  Per 32x32x16 MFMA
+// the tile loop reads one 1 KB operand fragment from LDS and issues, for the softmax of the one
+// score element a lane owns per MFMA (a wave's 32 x 64 scores take 32 MFMAs), one multiply-add,
+// one exp2, one add and half a conversion.  This
+// kernel issues exactly that per MFMA, with random operands, fragments read from LDS four steps
+// ahead, two waves per SIMD, and nothing else: no tile loads, no barriers, no masks, no item
+// boundaries.  The device runs it at its power limit like the attention kernel, so the rate is
+// the ceiling of the loop body on this device; mode 0 leaves out the LDS reads and the vector
+// work (the MFMA-only rate with two waves per SIMD), mode 1 adds the LDS reads, mode 2 adds both.
+__global__ __launch_bounds__(512) void mix_ceiling_kernel(unsigned long long* counters, int iters, int mode) {
+    typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x16 __attribute__((ext_vector_type(16)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    __shared__ u32x4 lds[4096];  // 64 KB of random 16-bit patterns
+    unsigned st = (blockIdx.x * 512 + threadIdx.x) * 2654435761u + 12345u;
+    auto rnd = [&]() {  // random sign and mantissa, exponent 126 or 127: magnitudes in [0.5, 2)
+        st = st * 1664525u + 1013904223u;
+        return (st & 0x807f807fu) | 0x3f003f00u | ((st >> 3) & 0x00800080u);
+    };
+    for (int i = threadIdx.x; i < 4096; i += 512) lds[i] = u32x4{rnd(), rnd(), rnd(), rnd()};
+    __syncthreads();
+    u32x4 a[4], b[4];
+    for (int n = 0; n < 4; ++n) {
+        a[n] = u32x4{rnd(), rnd(), rnd(), rnd()};
+        b[n] = u32x4{rnd(), rnd(), rnd(), rnd()};
+    }
+    f32x16 acc[4];
+    for (int n = 0; n < 4; ++n)
+        for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
+    float x[16];
+    for (int i = 0; i < 16; ++i) x[i] = -0.01f * (float)((st >> (i & 7)) & 255);
+    float rs0 = 0.f, rs1 = 0.f;
+    unsigned keep = 0;
+    const char* lb = reinterpret_cast<const char*>(lds) + ((threadIdx.x * 16) & 0x3ff0);
+    u32x4 ring[4];
+    for (int n = 0; n < 4; ++n) ring[n] = *reinterpret_cast<const u32x4*>(lb + n * 16384);
+    const unsigned long long c0 = clock64(), r0 = wall_clock64();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int n = 0; n < 16; ++n) {
+            const u32x4 av = mode >= 1 ? ring[n & 3] : a[n & 3];
+            acc[n & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, b[n & 3]), acc[n & 3], 0, 0, 0);
+            if (mode >= 1) ring[n & 3] = *reinterpret_cast<const u32x4*>(lb + (n & 3) * 16384);
+            if (mode >= 2) {
+                const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(x[n], 0.127517f, -0.25f));
+                if (n & 1) {
+                    rs1 += e;
+                    unsigned pk = __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{x[n - 1], e}, bf16x2));
+                    asm volatile("" : "+v"(pk));
+                    keep ^= pk;
+                } else {
+                    rs0 += e;
+                }
+                asm volatile("" : "+v"(x[n]));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    const unsigned long long c1 = clock64(), r1 = wall_clock64();
+    float sum = rs0 + rs1;
+    for (int n = 0; n < 4; ++n)
+        for (int v = 0; v < 16; ++v) sum += acc[n][v];
+    if (blockIdx.x == 7 && threadIdx.x == 0) {
+        counters[0] = c1 - c0;  // core clock cycles
+        counters[1] = r1 - r0;  // ticks of the constant 100 MHz clock
+    }
+    if (sum == 1.2345e-30f || keep == 0x12345678u) counters[2] = 1;  // keeps the results alive
 }
 
 // ---- measurement aid: what the vector ALU sustains on the softmax's own instruction mix.  Per
@@ -499,6 +572,31 @@ int attn_mfma_ceiling(int random_operands, int iters, void* stream, unsigned lon
     hipEventDestroy(e1);
     if (rc != ATTN_OK) return rc;
     *tflops = (double)blocks * 4 * (double)iters * 4 * 32768.0 / ((double)ms * 1e-3) / 1e12;
+    *core_ghz = h[1] ? (double)h[0] / ((double)h[1] * 10.0) : 0.0;
+    return ATTN_OK;
+}
+
+int attn_mix_ceiling(int mode, int iters, void* stream, unsigned long long* counters, double* tflops, double* core_ghz) {
+    if (mode < 0 || mode > 2 || iters < 1 || !counters || !tflops || !core_ghz) return ATTN_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const int blocks = cu_count();  // one workgroup of 8 waves per CU: two waves per SIMD
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return ATTN_ELAUNCH;
+    if (hipEventCreate(&e1) != hipSuccess) { hipEventDestroy(e0); return ATTN_ELAUNCH; }
+    int rc = ATTN_OK;
+    float ms = 0.f;
+    unsigned long long h[2] = {0, 0};
+    void* args[] = {&counters, &iters, &mode};
+    if (hipEventRecord(e0, s) != hipSuccess ||
+        hipLaunchKernel((const void*)mix_ceiling_kernel, dim3(blocks), dim3(512), args, 0, s) != hipSuccess ||
+        hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+        hipEventElapsedTime(&ms, e0, e1) != hipSuccess ||
+        hipMemcpy(h, counters, sizeof h, hipMemcpyDeviceToHost) != hipSuccess)
+        rc = ATTN_ELAUNCH;
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    if (rc != ATTN_OK) return rc;
+    *tflops = (double)blocks * 8 * (double)iters * 16 * 32768.0 / ((double)ms * 1e-3) / 1e12;
     *core_ghz = h[1] ? (double)h[0] / ((double)h[1] * 10.0) : 0.0;
     return ATTN_OK;
 }

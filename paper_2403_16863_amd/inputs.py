@@ -113,7 +113,7 @@ def make_qkv(w: Workload, seed: int):
 # Adversarial families used by the randomized admission tests.  Each returns
 # float32 arrays that are then rounded like the ordinary inputs.
 ADVERSARIAL = ("peaked", "equal_scores", "large_negative", "single_v_row", "signed_zero",
-               "max_finite_v")
+               "max_finite_v", "rising_scores")
 
 
 def make_adversarial(kind: str, B: int, H: int, N: int, d: int, dtype: int, seed: int):
@@ -147,6 +147,18 @@ def make_adversarial(kind: str, B: int, H: int, N: int, d: int, dtype: int, seed
         # fp32 range; the largest finite bfloat16 (3.4e38) cannot be averaged that way.
         big = 65504.0 if dtype == F16 else 2.0 ** 100
         v[:] = np.where(g.random(shape, dtype=np.float32) < 0.5, big, -big).astype(np.float32)
+    elif kind == "rising_scores":
+        # every query scores key j at about 3 * sqrt(d) * j / N (scaled by 1/sqrt(d)) plus noise: the
+        # scores climb by dozens over the sequence, tile after tile, and the last key is a peak on
+        # top.  A one-pass softmax has to move its reference maximum again and again, in the
+        # middle of the key stream and at its end.
+        u = g.standard_normal(d, dtype=np.float32)
+        u /= np.float32(np.linalg.norm(u))
+        root = np.float32(np.sqrt(d))
+        q[:] = q * np.float32(0.25) + u * root
+        ramp = (np.arange(N, dtype=np.float32) / np.float32(max(N, 1)))[None, None, :, None]
+        k[:] = k * np.float32(0.25) + np.float32(3.0) * ramp * u * root
+        k[:, :, N - 1, :] += np.float32(1.5) * u * root
     else:
         raise ValueError(kind)
     return f32_to_bits(q, dtype), f32_to_bits(k, dtype), f32_to_bits(v, dtype)

@@ -103,8 +103,16 @@ class Node:
     def is_vmem(self) -> bool:
         return self.kind == "unit" or (self.kind == "ins" and self.mnem.split("_")[0] in ("global", "buffer", "scratch", "flat"))
 
+    def is_smem(self) -> bool:      # scalar memory: returns out of order, counted by lgkmcnt too
+        return self.kind == "ins" and (self.mnem.startswith("s_load") or self.mnem.startswith("s_buffer_load") or
+                                       self.mnem.startswith("s_memtime") or self.mnem.startswith("s_memrealtime"))
+
+    def is_register_load(self) -> bool:   # a tile load into registers (the staged load path)
+        return self.kind == "ins" and self.mnem.startswith(("buffer_load_dword", "global_load_dword")) and "lds" not in self.lines[0]
+
     def is_movable(self) -> bool:
-        return self.in_loop and (self.kind == "unit" or (self.kind == "ins" and self.mnem.startswith("ds_read")))
+        return self.in_loop and (self.kind == "unit" or self.is_register_load() or
+                                 (self.kind == "ins" and self.mnem.startswith("ds_read")))
 
     def valu_writes_scalar(self) -> bool:
         return self.kind == "ins" and self.mnem.startswith("v_") and any(r[0] in "sem" or r == "vcc" for r in self.may_write)
@@ -149,7 +157,7 @@ def _make_ins(line: str) -> Node:
         n.mentions.add("m0")       # direct-to-LDS loads take their LDS base from M0
     if mnem.startswith(("v_readlane", "v_readfirstlane")):
         pass                        # scalar destination is operand 0 already
-    if mnem.startswith("ds_read"):
+    if mnem.startswith("ds_read") or (mnem.startswith(("buffer_load_dword", "global_load_dword")) and "lds" not in body):
         n.defs = regs_of(ops[0])
         n.uses = regs_of(",".join(ops[1:]))
     n.mentions |= n.may_write
@@ -292,6 +300,25 @@ def _scalar_writer_near(nodes: List[Node], i: int, window: int = 6) -> bool:
     return False
 
 
+def _smem_before_wait(nodes: List[Node], j: int) -> bool:
+    """True if a scalar memory operation is issued between the wait at index j and the previous
+    point where the lgkm counter is known to be zero (an `lgkmcnt(0)` wait) or the start of the
+    basic block.  Scalar loads return out of order, so a wait that may cover one only means
+    something as `lgkmcnt(0)`: its count must not be changed and nothing counted may cross it."""
+    k = j - 1
+    while k >= 0:
+        n = nodes[k]
+        if n.kind == "label" or (n.kind == "ins" and n.is_fence()):
+            return False
+        if n.kind == "ins":
+            if n.is_smem():
+                return True
+            if n.mnem == "s_waitcnt" and _wait_fields(n)[1] == 0:
+                return False
+        k -= 1
+    return False
+
+
 def try_move(nodes: List[Node], i: int, direction: int) -> Optional[List[Node]]:
     """Move the movable node at index i by one instruction up (-1) or down (+1).  Returns the
     new node list, or None if the move is not allowed."""
@@ -318,6 +345,8 @@ def try_move(nodes: List[Node], i: int, direction: int) -> Optional[List[Node]]:
             if names_vm:
                 return None                       # a wait for tile loads is what makes LDS contents valid: reads stay behind it
             if lgkm is not None:
+                if _smem_before_wait(nodes, j):
+                    return None                   # the wait may guard a scalar load: leave it alone
                 if direction < 0:                 # read moves above the wait: one more operation in flight there
                     if lgkm + 1 > LGKM_MAX:
                         return None
@@ -434,13 +463,13 @@ def assemble(asm_text: str, workdir: str, tag: str) -> str:
 def knobs_of_variant(variant: int) -> List[int]:
     from . import binding as B
     desc = dict(kv.split("=") for kv in B.attn_variant_desc(variant).split())
-    return [int(desc[k]) for k in ("bn", "nw", "qb", "occ", "ldp", "pipe", "pf", "prio")]
+    return [int(desc[k]) for k in ("bn", "nw", "qb", "occ", "ldp", "pipe", "pf", "prio", "ilv", "ldpos")]
 
 
 class GpuRunner:
     """Loads candidates, tests them against the unmodified kernel and times them."""
 
-    def __init__(self, kernel: Kernel, variant: int, workload, workdir: str, samples: int = 16, seed: int = 0):
+    def __init__(self, kernel: Kernel, variant: int, workload, workdir: str, samples: int = 64, seed: int = 0):
         import torch
         from . import binding as B
         from .search import _device_inputs
@@ -467,18 +496,17 @@ class GpuRunner:
         return self._handles[key]
 
     def admit(self, s: Schedule) -> bool:
-        """Probabilistic test of Sec. 4.2 against the unmodified kernel (the variant's own)."""
-        import math
+        """Probabilistic test of Sec. 4.2 against the unmodified kernel (the variant's own).  A
+        re-ordered copy performs the same floating-point operations in the same order, so its
+        output has to be bit-identical: any difference, however small, rejects the candidate
+        (the wait-state rules between arithmetic instructions are not modelled, this test is the
+        guard).  Inputs: random tensors of ragged and long shapes plus the adversarial families,
+        among them scores that rise from tile to tile, which run the rarely taken path that
+        raises the reference maximum in the middle of the stream."""
         torch, B, w = self.torch, self.B, self.w
-        from .search import _device_inputs
+        from .search import admission_inputs
         h = self.handle(s)
-        rng = random.Random(self.seed)
-        tol_o = 1e-2 if w.dtype == 0 else 3e-2
-        shapes = [(1, 2, 1), (1, 1, 17), (2, 2, 127), (1, 2, 129), (1, 3, 1000), (2, 2, 384), (1, 4, 2048), (1, 8, 1024)]
-        for i in range(self.samples):
-            Bs, H, N = shapes[i % len(shapes)]
-            q, k, v = _device_inputs(Bs, H, N, w.d, w.dtype, rng.randrange(1 << 30), rng.choice((1.0, 1.0, 2.0)))
-            scale = 1.0 / math.sqrt(w.d)
+        for q, k, v, scale in admission_inputs(w.d, w.dtype, self.samples, self.seed):
             ref_o = torch.empty_like(q)
             ref_l = torch.empty(q.shape[:3], dtype=torch.float32, device="cuda")
             B.attn_fwd_variant(q, k, v, ref_o, ref_l, w.causal, scale, self.variant)
@@ -486,11 +514,9 @@ class GpuRunner:
             lse = torch.full_like(ref_l, float("nan"))
             B.attn_fwd_codeobj(h, q, k, v, out, lse, w.causal, scale)
             torch.cuda.synchronize()
-            if not (torch.isfinite(out).all() and torch.isfinite(lse).all()):
+            if not torch.equal(out.view(torch.int16), ref_o.view(torch.int16)):
                 return False
-            if (out.float() - ref_o.float()).abs().max().item() > tol_o:
-                return False
-            if ((lse - ref_l).abs() / ref_l.abs().clamp(min=1.0)).max().item() > 1e-3:
+            if not torch.equal(lse.view(torch.int32), ref_l.view(torch.int32)):
                 return False
         return True
 
@@ -501,7 +527,7 @@ class GpuRunner:
 
 
 def search_workload(widx: int, seed: int = 0, t_max: float = 0.05, t_min: float = 5e-4, cool: float = 1.05,
-                    samples: int = 16, variant: Optional[int] = None, db_path: Optional[str] = None,
+                    samples: int = 64, variant: Optional[int] = None, db_path: Optional[str] = None,
                     keep_best: Optional[str] = None, verbose: bool = False, validate_rounds: int = 7) -> dict:
     """Simulated annealing (Alg. 1) over instruction positions of the kernel a workload uses."""
     from . import binding as B
@@ -695,7 +721,7 @@ def main(argv: Optional[Sequence[str]] = None) -> None:
     ap.add_argument("--tmax", type=float, default=0.05)
     ap.add_argument("--tmin", type=float, default=5e-4)
     ap.add_argument("--cool", type=float, default=1.05)
-    ap.add_argument("--samples", type=int, default=16, help="random inputs per admission test")
+    ap.add_argument("--samples", type=int, default=64, help="random inputs per admission test")
     ap.add_argument("--db", type=str, default=None, help="append every step as JSON lines to this file")
     ap.add_argument("--keep-best", type=str, default=None, help="write the best kernel's assembly to this file")
     ap.add_argument("--verbose", action="store_true")

@@ -46,13 +46,45 @@ def test_benchmark_configs_full(idx):
         check(O, l, O_ref, l_ref, w.dtype, what=f"{w.label} var={var}")
 
 
-@pytest.mark.parametrize("idx,nrows", [(2, 1024), (3, 384), (4, 2048)])
+def boundary_and_round_rows(w, bm=256):
+    """Rows the launch configuration makes special: both sides of every query-tile boundary of
+    one head (first, last and the rows next to them of every tile), and rows of the work items
+    that the first and the last workgroup take in every round of the persistent schedule."""
+    import paper_2403_16863_amd as A
+    rows = set()
+    nqt = (w.N + bm - 1) // bm
+    head = (w.B * w.H) // 2
+    for t in range(nqt):
+        for i in (t * bm, t * bm + 1, t * bm + bm // 2, min(w.N, (t + 1) * bm) - 2, min(w.N, (t + 1) * bm) - 1):
+            if 0 <= i < w.N:
+                rows.add(head * w.N + i)
+    var = A.attn_default_variant(w.N, w.d, w.dtype, w.causal)
+    grid = A.attn_schedule_grid(var, 256, w.B, w.H, w.N)
+    for wg in (0, grid // 2, grid - 1):
+        rnd = 0
+        while True:
+            item = A.attn_schedule_item(grid, wg, w.B * w.H, nqt, rnd)
+            if item is None:
+                break
+            bh, qt = item
+            for i in (qt * bm, qt * bm + 33, min(w.N, (qt + 1) * bm) - 1):
+                if i < w.N:
+                    rows.add(bh * w.N + i)
+            rnd += 1
+    return rows
+
+
+@pytest.mark.parametrize("idx,nrows", [(2, 8192), (3, 16384), (4, 4096)])
 def test_benchmark_configs_sampled(idx, nrows):
     """Full-size workloads in the launch configuration bench.py times, compared on
-    sampled rows the oracle computes one by one; every output must be finite."""
+    sampled rows the oracle computes one by one (random rows of every head, both sides of every
+    query-tile boundary of one head, rows of every round of the schedule); every output must
+    be finite."""
     w = I.WORKLOADS[idx]
     qb, kb, vb = I.make_qkv(w, seed=idx)
-    rows = I.sample_rows(w, nrows, seed=idx)
+    rows = set(int(r) for r in I.sample_rows(w, nrows, seed=idx))
+    rows |= boundary_and_round_rows(w, 256 if w.d == 128 else 128)
+    rows = np.array(sorted(rows), dtype=np.int64)
     O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, w.causal, w.scale, w.dtype, rows=rows)
     print(f"case {w.label} default variant", flush=True)
     O, l = run_gpu(qb, kb, vb, w.causal, w.scale, w.dtype)
@@ -65,7 +97,7 @@ def test_benchmark_configs_sampled(idx, nrows):
 
 
 @pytest.mark.parametrize("B,H,N,d,causal,dtype,nrows", [
-    (1, 1, 65536, 128, True, I.BF16, 256),      # one very long sequence: 256 query tiles of one head
+    (1, 1, 65536, 128, True, I.BF16, 3072),     # one very long sequence: 256 query tiles of one head
     (1, 2, 40000, 64, False, I.F16, 192),       # long, ragged (40000 = 625 * 64), no mask
     (64, 64, 64, 64, True, I.F16, 1024),        # 4096 heads of one tile each: more work items than workgroups
     (3, 37, 257, 128, True, I.BF16, 1024),      # head count without a factor of 8, one row past a tile
@@ -77,7 +109,10 @@ def test_extreme_shapes_sampled(B, H, N, d, causal, dtype, nrows):
     head counts that do not divide over the XCDs), compared on sampled rows; every output finite."""
     w = I.Workload("extreme", B, H, N, d, causal, dtype)
     qb, kb, vb = I.make_qkv(w, seed=N)
-    rows = I.sample_rows(w, nrows, seed=N)
+    rows = set(int(r) for r in I.sample_rows(w, nrows, seed=N))
+    if N >= 4096:
+        rows |= boundary_and_round_rows(w, 256 if d == 128 else 128)
+    rows = np.array(sorted(rows), dtype=np.int64)
     O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, w.causal, w.scale, w.dtype, rows=rows)
     print(f"case {w.label} default variant", flush=True)
     O, l = run_gpu(qb, kb, vb, w.causal, w.scale, w.dtype)
@@ -97,6 +132,24 @@ def test_adversarial_inputs(kind, dtype):
             print(f"case {kind} N={N} d={d} causal={causal} dtype={dtype} variant={var}", flush=True)
             O, l = run_gpu(qb, kb, vb, causal, scale, dtype, variant=var)
             check(O, l, O_ref, l_ref, dtype, out_scale=out_scale, what=f"{kind} var={var}")
+
+
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("d", [64, 128])
+def test_reference_maximum_raised_in_mid_stream_all_variants(d, dtype):
+    """Scores that climb by dozens from the first key to the last, tile after tile, with a peak on
+    the last key: every variant has to raise its reference maximum in the middle of the key
+    stream and at its end (for the interleaved and the two-cluster orders that path sits inside
+    the pipelined MFMA streams), with and without the causal mask, past several tiles."""
+    for N, causal in ((512, False), (640, True), (1100, False), (1100, True)):
+        qb, kb, vb = I.make_adversarial("rising_scores", 1, 2, N, d, dtype, seed=N + d)
+        scale = float(np.float32(1.0 / np.sqrt(d)))
+        O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, causal, scale, dtype)
+        out_scale = max(1.0, float(np.abs(I.bits_to_f64(vb, dtype)).max()))
+        for var in [None] + variants_for(d, dtype, causal):
+            print(f"case rising N={N} d={d} causal={causal} dtype={dtype} variant={var}", flush=True)
+            O, l = run_gpu(qb, kb, vb, causal, scale, dtype, variant=var)
+            check(O, l, O_ref, l_ref, dtype, out_scale=out_scale, what=f"rising N={N} causal={causal} var={var}")
 
 
 def test_scale_argument_and_stream():

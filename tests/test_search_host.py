@@ -131,3 +131,61 @@ def test_lattice_of_the_built_library_is_walkable():
     f = lambda c: 1.0 + 0.01 * lat.points[c]
     res = S.anneal(lat, movable[0], f, lambda c: True, seed=1)
     assert res.best in lat.points and res.t_best <= res.t0
+
+
+def test_store_resumes_a_killed_search_on_the_same_trajectory(tmp_path):
+    """Sec. 4.1: every candidate is stored; a search that was cut short continues from the file
+    to exactly the run it would have been, without repeating a measurement or a test."""
+    lat = box([4, 4, 3], holes={(2, 2, 1)})
+    x0 = (0, 0, 0)
+    calls = {"measure": 0, "admit": 0}
+
+    def measure(c):
+        calls["measure"] += 1
+        return bowl((3, 2, 1))(c) + 1e-3 * ((hash(c) % 7) - 3)
+
+    def admit(c):
+        calls["admit"] += 1
+        return c != (1, 0, 0)
+
+    header = {"workload": "toy", "seed": 5, "t_max": 0.05, "t_min": 5e-4, "cool": 1.05, "x0": list(x0)}
+    full = S.anneal(lat, x0, measure, admit, seed=5)
+
+    path = str(tmp_path / "search.jsonl")
+    store = S.SearchStore(path, header)
+    assert store.resume() == 0
+    store.open(measure(x0))
+
+    class Killed(Exception):
+        pass
+
+    def log_then_die(st):
+        store.log(st)
+        if st.step == 30:
+            raise Killed
+
+    with pytest.raises(Killed):
+        S.anneal(lat, x0, measure, admit, seed=5, log=log_then_die)
+    store.close()
+
+    again = S.SearchStore(path, header)
+    assert again.resume() == 31
+    again.open(0.0)
+    before = dict(calls)
+    seen_before = set(again.known_times) | set(again.known_admitted)
+    res = S.anneal(lat, x0, measure, admit, seed=5, log=again.log, known_times=again.known_times,
+                   known_admitted=again.known_admitted)
+    again.close()
+    assert [(s.candidate, s.accepted, s.best) for s in res.steps] == [(s.candidate, s.accepted, s.best) for s in full.steps]
+    assert res.best == full.best and res.t_best == full.t_best
+    # nothing that was stored was measured or tested again
+    new_points = {s.candidate for s in res.steps} - seen_before
+    assert calls["measure"] - before["measure"] <= len(new_points)
+    assert calls["admit"] - before["admit"] <= len(new_points)
+    # the file now holds the whole run, each step once, and resumes to a finished search
+    done = S.SearchStore(path, header)
+    assert done.resume() == len(full.steps)
+    # a store of another search is refused
+    other = S.SearchStore(path, dict(header, seed=6))
+    with pytest.raises(ValueError):
+        other.resume()

@@ -144,6 +144,41 @@ def test_wait_counter_bookkeeping():
         assert sip.try_move(k.nodes, _idx(k, "ds_read"), +1) is None, wait
 
 
+def test_scalar_loads_pin_their_wait():
+    """A wait that may guard a scalar load (these return out of order) is neither crossed nor
+    re-counted: the snippet is the case where an `lgkmcnt(0)` protects an `s_load` result."""
+    k = _mini(["s_load_dwordx2 s[4:5], s[0:1], 0x10", "ds_read_b128 v[8:11], v2", "s_waitcnt lgkmcnt(0)", "ds_read_b128 v[4:7], v1",
+               "v_mov_b32_e32 v40, v41"])
+    assert sip.try_move(k.nodes, _idx(k, "v[4:7]"), -1) is None     # would turn the wait into lgkmcnt(1)
+    assert sip.try_move(k.nodes, _idx(k, "v[8:11]"), +1) is None    # the wait covers it anyway
+    k = _mini(["s_load_dword s4, s[0:1], 0x0", "s_waitcnt lgkmcnt(1)", "ds_read_b128 v[4:7], v1"])
+    assert sip.try_move(k.nodes, _idx(k, "ds_read"), -1) is None
+    # once the counter is known to be zero behind the scalar load, waits further down are ordinary again
+    k = _mini(["s_load_dword s4, s[0:1], 0x0", "s_waitcnt lgkmcnt(0)", "v_mov_b32_e32 v40, v41", "s_waitcnt lgkmcnt(2)",
+               "ds_read_b128 v[4:7], v1"])
+    up = sip.try_move(k.nodes, _idx(k, "ds_read"), -1)
+    assert up is not None and "lgkmcnt(3)" in "\n".join(n.text for n in up)
+    # a basic-block boundary also ends the look-back
+    k = _mini(["s_load_dword s4, s[0:1], 0x0", "s_cbranch_scc1 .L1", "s_waitcnt lgkmcnt(2)", "ds_read_b128 v[4:7], v1"])
+    assert sip.try_move(k.nodes, _idx(k, "ds_read"), -1) is not None
+
+
+def test_register_tile_loads_move_like_the_papers_loads():
+    """Tile loads into registers (the staged load path) are part of the pruned space: they move
+    past arithmetic, never past another vector-memory operation, a vmcnt wait, or an instruction
+    that touches their registers."""
+    k = _mini(["v_mov_b32_e32 v40, v41", "buffer_load_dwordx4 v[4:7], v9, s[4:7], s12 offen", "v_mov_b32_e32 v42, v43"])
+    i = _idx(k, "buffer_load")
+    assert k.nodes[i].is_movable() and k.nodes[i].is_vmem()
+    assert sip.try_move(k.nodes, i, -1) is not None and sip.try_move(k.nodes, i, +1) is not None
+    for blocker in ("s_waitcnt vmcnt(2)", "buffer_load_dwordx4 v[12:15], v9, s[4:7], s13 offen", "v_mov_b32_e32 v9, v50",
+                    "v_add_f32_e32 v60, v5, v5", "global_store_dwordx4 v[0:1], v[20:23], off"):
+        k = _mini(["buffer_load_dwordx4 v[4:7], v9, s[4:7], s12 offen", blocker])
+        assert sip.try_move(k.nodes, _idx(k, "v[4:7]"), +1) is None, blocker
+    k = _mini(["v_mov_b32_e32 v40, v41", "buffer_load_dwordx4 v9, s[4:7], s12 offen lds"])
+    assert not k.nodes[_idx(k, "buffer_load")].is_movable()          # a load to LDS outside its hand-written group stays
+
+
 def test_tile_load_unit():
     unit = [";;#ASMSTART", "s_mov_b32 m0, s26", "s_nop 0", "global_load_lds_dwordx4 v217, s[0:1]", ";;#ASMEND"]
     k = _mini(["v_mov_b32_e32 v40, v41"] + unit + ["v_mov_b32_e32 v42, v43"])
