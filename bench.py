@@ -67,27 +67,31 @@ class DeviceSampler(threading.Thread):
         self.period = period_s
         self.stop_flag = threading.Event()
         self.clock_mhz, self.power_w = [], []
-        self.freq_files, self.power_files = [], []
-        roots = []
+        self.freq_files, self.power_files, self.cap_w = [], [], None
+        devs = []
         try:
             import torch
             pr = torch.cuda.get_device_properties(0)
             bus = f"{getattr(pr, 'pci_domain_id', 0):04x}:{pr.pci_bus_id:02x}:{pr.pci_device_id:02x}.0"
-            roots = glob.glob(f"/sys/bus/pci/devices/{bus}/hwmon/hwmon*")
+            devs = glob.glob(f"/sys/bus/pci/devices/{bus}")
         except Exception:
-            roots = []
-        self.source = "sysfs hwmon of the PCI device of cuda:0" if roots else "sysfs hwmon, busiest card"
-        if not roots:
-            roots = glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*")
-        for r in roots:
-            f = os.path.join(r, "freq1_input")
+            devs = []
+        self.source = "sysfs (pp_dpm_sclk, hwmon) of the PCI device of cuda:0" if devs else "sysfs (pp_dpm_sclk, hwmon), busiest card"
+        if not devs:
+            devs = glob.glob("/sys/class/drm/card*/device")
+        for dev in devs:
+            f = os.path.join(dev, "pp_dpm_sclk")       # lines "n: <MHz>Mhz", the current one marked with *
             if os.path.exists(f):
                 self.freq_files.append(f)
-            for name in ("power1_average", "power1_input"):
-                pf = os.path.join(r, name)
-                if os.path.exists(pf):
-                    self.power_files.append(pf)
-                    break
+            for r in glob.glob(os.path.join(dev, "hwmon", "hwmon*")):
+                for name in ("power1_average", "power1_input"):
+                    pf = os.path.join(r, name)
+                    if os.path.exists(pf):
+                        self.power_files.append(pf)
+                        break
+                cap = self._read(os.path.join(r, "power1_cap"))
+                if cap:
+                    self.cap_w = cap / 1e6
 
     @staticmethod
     def _read(path):
@@ -97,9 +101,20 @@ class DeviceSampler(threading.Thread):
         except Exception:
             return None
 
+    @staticmethod
+    def _read_sclk(path):
+        try:
+            with open(path) as fh:
+                for line in fh:
+                    if "*" in line:
+                        return float(line.split(":")[1].lower().replace("mhz", "").replace("*", "").strip()) * 1e6
+        except Exception:
+            pass
+        return None
+
     def run(self):
         while not self.stop_flag.is_set():
-            fr = [x for x in (self._read(f) for f in self.freq_files) if x]
+            fr = [x for x in (self._read_sclk(f) for f in self.freq_files) if x]
             pw = [x for x in (self._read(f) for f in self.power_files) if x]
             if fr:
                 self.clock_mhz.append(max(fr) / 1e6)
@@ -111,7 +126,7 @@ class DeviceSampler(threading.Thread):
         import numpy as np
         return {"core_clock_GHz": float(np.median(self.clock_mhz)) / 1e3 if self.clock_mhz else None,
                 "socket_power_W": float(np.median(self.power_w)) if self.power_w else None,
-                "samples": len(self.clock_mhz), "source": self.source}
+                "power_cap_W": self.cap_w, "samples": max(len(self.clock_mhz), len(self.power_w)), "source": self.source}
 
 
 def settle(A, w, tensors, variant, gpu_seconds=SETTLE_GPU_SECONDS):

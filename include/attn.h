@@ -188,7 +188,8 @@ int attn_mfma_ceiling(int random_operands, int iters, void* stream, unsigned lon
  * issues one multiply-add, one exp2, one add and half a conversion to 16 bit per lane for the
  * softmax.  The kernel issues that and nothing else (random operands, fragments read four steps
  * ahead, two waves per SIMD, `iters` rounds of 16 MFMAs per wave; no tile loads, barriers, masks
- * or item boundaries): mode 0 = MFMAs only, 1 = MFMAs and LDS reads, 2 = the whole mix.  The
+ * or item boundaries; launched twice, the second launch is the one timed): mode 0 = MFMAs only,
+ * 1 = MFMAs and LDS reads, 2 = the whole mix.  The
  * device runs it at its power limit, as it runs the attention kernel, so *tflops (host) is what
  * the loop body can reach there; *core_ghz (host) is the clock during the run (0 if the clock
  * counters could not be read).  counters: device memory, 3 x 8 bytes, written by the kernel

@@ -281,7 +281,7 @@ def attn_mfma_ceiling(random_operands: bool, iters: int = 300000):
     return tf.value, ghz.value
 
 
-def attn_mix_ceiling(mode: int, iters: int = 20000):
+def attn_mix_ceiling(mode: int, iters: int = 150000):
     """(TFLOP/s, core clock in GHz) of the tile loop's own instruction mix; see the header."""
     import torch
     counters = torch.zeros(3, dtype=torch.int64, device="cuda")

@@ -361,9 +361,14 @@ STORE_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "search_sto
 
 def search_workload(widx: int, seed: int = 0, t_max: float = 0.05, t_min: float = 5e-4,
                     cool: float = 1.05, samples: int = 64, db_path: Optional[str] = None,
-                    verbose: bool = False, resume: bool = False, store_ranking: bool = False) -> dict:
+                    verbose: bool = False, resume: bool = False, store_ranking: bool = False,
+                    start_variant: Optional[int] = None) -> dict:
     """Run the annealing search on one of the benchmark workloads and report the best
-    admitted variant next to the library default."""
+    admitted variant next to the library default.  The search starts at the library default, or
+    at `start_variant`: annealing at these temperatures does not cross a ridge of much slower
+    variants, so rounds from several starting points are what fills the ranking (Sec. 4.1: the
+    candidates of several rounds are stored and ranked together); with `store_ranking` a
+    round's candidates are merged into the stored ranking of the workload."""
     import torch
     from . import binding as Bd
     from . import inputs as I
@@ -374,7 +379,10 @@ def search_workload(widx: int, seed: int = 0, t_max: float = 0.05, t_min: float 
     lse = torch.empty(q.shape[:3], dtype=torch.float32, device="cuda")
     tensors = (q, k, v, out, lse)
     default = Bd.attn_default_variant(w.N, w.d, w.dtype, w.causal)
-    x0 = tuple(Bd.attn_variant_coords(default))
+    start = default if start_variant is None else int(start_variant)
+    if not Bd.attn_variant_supported(start, w.d, w.dtype, w.causal):
+        raise ValueError(f"variant {start} is not built for this workload")
+    x0 = tuple(Bd.attn_variant_coords(start))
     store = None
     if db_path:
         store = SearchStore(db_path, {"workload": w.name, "seed": seed, "t_max": t_max, "t_min": t_min, "cool": cool,
@@ -386,7 +394,7 @@ def search_workload(widx: int, seed: int = 0, t_max: float = 0.05, t_min: float 
             raise ValueError(f"{db_path} exists: pass --resume to continue that search, or name another file")
     # settle the device's clock before anything is timed (the first tens of milliseconds under load run faster)
     for _ in range(3):
-        measure_variant(tensors, w.causal, w.scale, default, warmup=0, iters=50)
+        measure_variant(tensors, w.causal, w.scale, start, warmup=0, iters=50)
 
     def log(st: Step):
         if store:
@@ -397,7 +405,7 @@ def search_workload(widx: int, seed: int = 0, t_max: float = 0.05, t_min: float 
     known_t = dict(store.known_times) if store else {}
     known_a = dict(store.known_admitted) if store else {}
     if store:
-        t0 = known_t[x0] if x0 in known_t else measure_variant(tensors, w.causal, w.scale, default)
+        t0 = known_t[x0] if x0 in known_t else measure_variant(tensors, w.causal, w.scale, start)
         known_t[x0] = t0
         store.open(t0)
     res = anneal(lat, x0,
@@ -407,32 +415,47 @@ def search_workload(widx: int, seed: int = 0, t_max: float = 0.05, t_min: float 
     if store:
         store.close()
     rank = res.ranking()
+    times_by_variant = {lat.points[c]: t for c, t in rank}
+    rejected = [lat.points[c] for c in res.rejected]
+    rank_path = os.path.join(STORE_DIR, f"ranking_{w.name}.json")
+    rounds = []
+    if store_ranking and os.path.exists(rank_path):     # merge with the rounds stored before
+        with open(rank_path) as fh:
+            old = json.load(fh)
+        rounds = old.get("rounds", [])
+        for e in old.get("ranking", []):
+            times_by_variant.setdefault(int(e["variant"]), float(e["ms"]))
+        rejected = sorted(set(rejected) | set(old.get("rejected", [])))
+    merged = sorted(times_by_variant.items(), key=lambda kv: kv[1])
     # the leaders, the default and variant 0 (the first hand-written schedule) once more, in alternation
-    leaders = [lat.points[c] for c, _ in rank[:3]]
+    leaders = [v for v, _ in merged[:3]]
     again = list(dict.fromkeys(leaders + [default] + ([0] if Bd.attn_variant_supported(0, w.d, w.dtype, w.causal) else [])))
     val = validate_leaders(tensors, w.causal, w.scale, again)
     best_v = min(leaders, key=lambda v: val[v])
     report = {
         "workload": w.label, "seed": seed, "steps": len(res.steps),
-        "default_variant": default, "default_desc": Bd.attn_variant_desc(default), "default_ms": res.t0,
+        "start_variant": start, "start_ms": res.t0,
+        "default_variant": default, "default_desc": Bd.attn_variant_desc(default), "default_ms": times_by_variant.get(default),
         "best_variant": lat.points[res.best], "best_desc": Bd.attn_variant_desc(lat.points[res.best]),
-        "best_ms": res.t_best, "gain_over_default": res.t0 / res.t_best,
+        "best_ms": res.t_best, "gain_over_start": res.t0 / res.t_best,
         "validated": {"ms": {str(v): t for v, t in val.items()}, "best_variant": best_v,
                       "best_vs_default": val[default] / val[best_v],
                       "best_vs_variant0": (val[0] / val[best_v]) if 0 in val else None},
-        "visited": len(res.times), "rejected": [lat.points[c] for c in res.rejected],
-        "ranking": [{"variant": lat.points[c], "ms": t} for c, t in rank],
+        "visited": len(res.times), "rejected": rejected,
+        "ranking": [{"variant": v, "ms": t} for v, t in merged],
         "paper_context": "A100 speed-ups reported by the paper: 1.062x (attention), 1.123x (GEMM+LeakyReLU)",
     }
     if store_ranking:
         os.makedirs(STORE_DIR, exist_ok=True)
-        summary = {"workload": w.label, "measured_on": torch.cuda.get_device_name(0), "seed": seed, "steps": len(res.steps),
+        rounds.append({"seed": seed, "start_variant": start, "steps": len(res.steps), "visited": len(res.times),
+                       "best_of_round": lat.points[res.best]})
+        summary = {"workload": w.label, "measured_on": torch.cuda.get_device_name(0), "rounds": rounds,
                    "admission_samples": samples, "default_variant": default, "best_variant": best_v,
                    "best_desc": Bd.attn_variant_desc(best_v), "best_vs_default": report["validated"]["best_vs_default"],
                    "best_vs_variant0": report["validated"]["best_vs_variant0"],
                    "validated_ms": report["validated"]["ms"], "ranking": report["ranking"],
                    "rejected": report["rejected"]}
-        with open(os.path.join(STORE_DIR, f"ranking_{w.name}.json"), "w") as fh:
+        with open(rank_path, "w") as fh:
             json.dump(summary, fh, indent=1)
             fh.write("\n")
     return report
@@ -450,10 +473,11 @@ def main(argv: Optional[Sequence[str]] = None) -> None:
     ap.add_argument("--resume", action="store_true", help="continue the search stored in --db")
     ap.add_argument("--store-ranking", action="store_true",
                     help="write the validated ranking to the package's search_store/ (read by bench.py)")
+    ap.add_argument("--start", type=int, default=None, help="variant the search starts at (default: the library default)")
     ap.add_argument("--verbose", action="store_true")
     a = ap.parse_args(argv)
     print(json.dumps(search_workload(a.workload, a.seed, a.tmax, a.tmin, a.cool, a.samples, a.db, a.verbose,
-                                     a.resume, a.store_ranking)))
+                                     a.resume, a.store_ranking, a.start)))
 
 
 if __name__ == "__main__":
