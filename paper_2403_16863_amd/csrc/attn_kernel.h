@@ -727,8 +727,10 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
             // check of the buffer descriptor), so ragged tails need neither a branch nor a clamp;
             // their scores are masked.  which = 0: K, 1: V; piece = 0, 1 (NT chunks each).
             static_assert(LD_PER_THREAD == 2, "two pieces per tile and lane");
-            const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(Kh), 0, N * RB, 0x00020000);
-            const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(Vh), 0, N * RB, 0x00020000);
+            // (descriptor: base, stride 0, number of bytes, and the flag word of an untyped 32-bit buffer)
+            const int head_bytes = (int)((unsigned)N * (unsigned)RB);  // below 2^32: checked by the host before the launch
+            const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(Kh), 0, head_bytes, 0x00020000);
+            const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(Vh), 0, head_bytes, 0x00020000);
             auto tile_load = [&](int which, int tile, int buf, int piece) __attribute__((always_inline)) {
                 constexpr int ROWS_PER_PIECE = NT / CPR;
                 char* dst = smem_b + buf * 2 * TILE_BYTES + which * TILE_BYTES + (piece * NT + wave * 64) * 16;

@@ -16,7 +16,7 @@ from paper_2403_16863_amd import inputs as I
 from tests.gpu_util import O_TOL, LSE_RTOL, run_gpu
 
 FAMILIES = ("normal", "normal", "normal", "wide", "peaked", "equal_scores", "large_negative",
-            "single_v_row", "signed_zero", "max_finite_v")
+            "single_v_row", "signed_zero", "max_finite_v", "rising_scores")
 # sequence lengths around every tile boundary of the shipped variants, plus odd ones
 LENGTHS = (1, 2, 17, 31, 32, 33, 63, 64, 65, 100, 127, 128, 129, 191, 192, 193, 255, 256, 257, 300, 383, 384,
            385, 511, 512, 513, 640, 777, 1000, 1024, 1025)

@@ -152,6 +152,40 @@ def test_reference_maximum_raised_in_mid_stream_all_variants(d, dtype):
             check(O, l, O_ref, l_ref, dtype, out_scale=out_scale, what=f"rising N={N} causal={causal} var={var}")
 
 
+@pytest.mark.parametrize("dtype,vlim", [(I.F16, 10.0), (I.BF16, 3.75)])
+def test_accuracy_bound_at_the_stated_limit(dtype, vlim):
+    """The header's accuracy bound: the error is at most about 2 u Vmax (u = 2^-11 binary16, 2^-8
+    bfloat16), so the absolute tolerances hold for |V| up to 10 / 3.8 even when a row puts all its
+    weight on values of that size and one sign (rounding of P and the final rounding then add up).
+    Also the V magnitude limit: bfloat16 values of 2^110 with N = 129 keys stay finite and accurate
+    relative to their size."""
+    g = np.random.Generator(np.random.Philox(key=np.array([77, 5], dtype=np.uint64)))
+    for d, N, causal in ((128, 300, True), (64, 257, False), (128, 1000, False)):
+        shape = (1, 2, N, d)
+        q = g.standard_normal(shape, dtype=np.float32)
+        k = g.standard_normal(shape, dtype=np.float32)
+        v = (np.float32(vlim) * (np.float32(0.93) + np.float32(0.07) * g.random(shape, dtype=np.float32))).astype(np.float32)
+        qb, kb, vb = (I.f32_to_bits(x, dtype) for x in (q, k, v))
+        scale = float(np.float32(1.0 / np.sqrt(d)))
+        O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, causal, scale, dtype)
+        for var in [None] + variants_for(d, dtype, causal):
+            print(f"case bound |v|<={vlim} N={N} d={d} causal={causal} dtype={dtype} variant={var}", flush=True)
+            O, l = run_gpu(qb, kb, vb, causal, scale, dtype, variant=var)
+            check(O, l, O_ref, l_ref, dtype, what=f"|v|<={vlim} N={N} var={var}")
+            u = 2.0 ** -11 if dtype == I.F16 else 2.0 ** -8
+            assert np.max(np.abs(O - O_ref)) <= 2.05 * u * vlim, "outside the derived bound 2 u Vmax"
+    big = np.float32(2.0 ** 110)
+    shape = (1, 2, 129, 128)
+    q = g.standard_normal(shape, dtype=np.float32)
+    k = g.standard_normal(shape, dtype=np.float32)
+    v = np.where(g.random(shape, dtype=np.float32) < 0.5, big, -big).astype(np.float32)
+    qb, kb, vb = (I.f32_to_bits(x, I.BF16) for x in (q, k, v))
+    scale = float(np.float32(1.0 / np.sqrt(128)))
+    O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, False, scale, I.BF16)
+    O, l = run_gpu(qb, kb, vb, False, scale, I.BF16)
+    check(O, l, O_ref, l_ref, I.BF16, out_scale=float(big), what="V = +-2^110")
+
+
 def test_scale_argument_and_stream():
     """Non-default scale, and a launch on a side stream."""
     import torch
