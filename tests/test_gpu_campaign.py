@@ -3,6 +3,8 @@ probabilistic testing of Sec. 4.2 / Sec. 5.2, with the oracle in the place of th
 kernel).  Every sample draws a shape, a dtype, a mask, an input family and a seed; the
 number of samples comes from ATTN_CAMPAIGN_SAMPLES (default 120: a few seconds).  Run as a
 script for a long campaign:  ATTN_CAMPAIGN_SAMPLES=5000 python -m pytest tests/test_gpu_campaign.py -m gpu -s
+With ATTN_CAMPAIGN_ALL_VARIANTS=1 every sample also draws one of the schedule variants built for
+its head dimension, instead of the library default (by default every fourth sample does).
 """
 import os
 import random
@@ -42,6 +44,10 @@ def test_campaign_against_oracle():
     worst_what = ""
     by_family = {}
     trace = os.environ.get("ATTN_CAMPAIGN_TRACE")  # file that names the sample in flight, for a run that dies
+    all_variants = os.environ.get("ATTN_CAMPAIGN_ALL_VARIANTS") == "1"
+    import paper_2403_16863_amd as A
+    vrng = random.Random(rng.randrange(1 << 30))     # its own stream: the draws above stay what they were
+    by_variant = {}
     print(f"campaign: {samples} samples to draw", flush=True)
     for n in range(samples):
         B, H, N, d, dtype, causal, fam, seed = draw(rng)
@@ -56,9 +62,13 @@ def test_campaign_against_oracle():
         if trace:
             with open(trace, "w") as f:
                 f.write(f"sample {n}: B{B} H{H} N{N} d{d} dtype{dtype} causal{causal} {fam} seed{seed}\n")
-        O, l = run_gpu(qb, kb, vb, causal, scale, dtype)
+        variant = None
+        if all_variants or n % 4 == 3:
+            variant = vrng.choice([v for v in range(A.attn_num_variants()) if A.attn_variant_supported(v, d, dtype, causal)])
+        by_variant[variant] = by_variant.get(variant, 0) + 1
+        O, l = run_gpu(qb, kb, vb, causal, scale, dtype, variant=variant)
         out_scale = max(1.0, float(np.abs(I.bits_to_f64(vb, dtype)).max())) if fam == "max_finite_v" else 1.0
-        what = f"sample {n}: B{B} H{H} N{N} d{d} dtype{dtype} causal{causal} {fam} seed{seed}"
+        what = f"sample {n}: B{B} H{H} N{N} d{d} dtype{dtype} causal{causal} {fam} seed{seed} variant{variant}"
         assert np.isfinite(O).all() and np.isfinite(l).all(), what
         eo = float(np.max(np.abs(O - O_ref))) / out_scale
         el = float(np.max(np.abs(l - l_ref) / np.maximum(1.0, np.abs(l_ref))))
@@ -71,7 +81,8 @@ def test_campaign_against_oracle():
         if (n + 1) % 250 == 0:
             print(f"campaign: {n + 1} samples passed, {time.time() - t0:.0f} s", flush=True)
     print(f"campaign: {samples} samples passed in {time.time() - t0:.1f} s; worst error as a fraction of the "
-          f"tolerance: O {worst_o:.3f} ({worst_what}), lse {worst_l:.3f}; families {by_family}", flush=True)
+          f"tolerance: O {worst_o:.3f} ({worst_what}), lse {worst_l:.3f}; families {by_family}; "
+          f"variants (None = library default) {dict(sorted(by_variant.items(), key=lambda kv: -1 if kv[0] is None else kv[0]))}", flush=True)
 
 
 @pytest.mark.gpu
