@@ -170,6 +170,29 @@ int attn_time_codeobj(int handle, const void* q, const void* k, const void* v, v
                       int B, int H, int N, int d, int causal, float scale, int dtype, void* stream,
                       int warmup, int iters, float* ms);
 
+/* Deployment of a searched schedule (Sec. 4.1: the candidates of the offline searches are
+ * ranked, and the best one that passed the tests is what the application runs, chosen once,
+ * at no cost per call).  After attn_deploy_variant, attn_fwd launches `variant_id` for every
+ * problem with this d, dtype and causal flag (0 / non-zero) and n_min <= N <= n_max, instead
+ * of attn_default_variant's choice; attn_deploy_codeobj does the same for a loaded code object
+ * (the instruction-level search's winner), for the d, dtype and causal flag it was loaded for.
+ * The newest matching entry wins.  A deployed schedule that refuses a problem
+ * (ATTN_EUNSUPPORTED, e.g. the interleaved order beyond 4 GiB per head) is replaced by the
+ * library default for that call.  attn_deployed reports what attn_fwd would launch for a
+ * shape: returns 1 and writes *variant_id (the schedule, or the schedule the code object was
+ * derived from) and *handle (the code object, -1 if none) when an entry matches, 0 when the
+ * default applies (*variant_id = the default, *handle = -1); either pointer may be NULL.
+ * attn_deploy_clear removes every entry; attn_codeobj_unload removes the entries of its handle.
+ * Up to 16 entries (ATTN_EUNSUPPORTED beyond, or if the variant was not built for the
+ * shape); ATTN_EINVAL for bad ids, handles or an empty range.  Host logic only: no device
+ * call, nothing is validated here (admission is the search's job, Sec. 4.2).  The table is
+ * process-wide and not synchronised, like the handle table: set it up from one thread
+ * before the launches that rely on it. */
+int attn_deploy_variant(int variant_id, int d, int dtype, int causal, int n_min, int n_max);
+int attn_deploy_codeobj(int handle, int n_min, int n_max);
+int attn_deploy_clear(void);
+int attn_deployed(int N, int d, int dtype, int causal, int* variant_id, int* handle);
+
 /* Measurement aid for the roofline (not part of the attention path): runs a kernel
  * that does nothing but independent 32x32x16 bf16 MFMAs from registers on every SIMD
  * (`iters` rounds of four per wave, 8 waves per CU) and reports the rate it sustained

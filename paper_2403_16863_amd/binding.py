@@ -21,7 +21,8 @@ SYMBOLS = ("attn_fwd", "attn_fwd_variant", "attn_num_variants", "attn_variant_su
            "attn_variant_coords", "attn_variant_from_coords", "attn_default_variant",
            "attn_time_variant", "attn_strerror", "attn_schedule_grid", "attn_schedule_item", "attn_mfma_ceiling",
            "attn_valu_ceiling", "attn_mix_ceiling",
-           "attn_codeobj_load", "attn_codeobj_unload", "attn_fwd_codeobj", "attn_time_codeobj")
+           "attn_codeobj_load", "attn_codeobj_unload", "attn_fwd_codeobj", "attn_time_codeobj",
+           "attn_deploy_variant", "attn_deploy_codeobj", "attn_deploy_clear", "attn_deployed")
 
 _lib = None
 
@@ -77,6 +78,14 @@ def lib():
         L.attn_codeobj_load.argtypes = [ctypes.c_char_p, ctypes.c_char_p, i, i, i, i]
         L.attn_codeobj_unload.restype = i
         L.attn_codeobj_unload.argtypes = [i]
+        L.attn_deploy_variant.restype = i
+        L.attn_deploy_variant.argtypes = [i, i, i, i, i, i]
+        L.attn_deploy_codeobj.restype = i
+        L.attn_deploy_codeobj.argtypes = [i, i, i]
+        L.attn_deploy_clear.restype = i
+        L.attn_deploy_clear.argtypes = []
+        L.attn_deployed.restype = i
+        L.attn_deployed.argtypes = [i, i, i, i, ctypes.POINTER(i), ctypes.POINTER(i)]
         L.attn_fwd_codeobj.restype = i
         L.attn_fwd_codeobj.argtypes = [i] + common
         L.attn_time_codeobj.restype = i
@@ -174,6 +183,36 @@ def attn_codeobj_unload(handle: int) -> None:
     rc = lib().attn_codeobj_unload(int(handle))
     if rc != ATTN_OK:
         raise AttnError(rc, "attn_codeobj_unload")
+
+
+def attn_deploy_variant(variant_id: int, d: int, dtype: int, causal: bool, n_min: int = 1, n_max: int = 2 ** 31 - 1) -> None:
+    """From now on attn_fwd launches this schedule for (d, dtype, causal) and n_min <= N <= n_max."""
+    rc = lib().attn_deploy_variant(int(variant_id), int(d), int(dtype), int(bool(causal)), int(n_min), int(n_max))
+    if rc != ATTN_OK:
+        raise AttnError(rc, f"attn_deploy_variant({variant_id})")
+
+
+def attn_deploy_codeobj(handle: int, n_min: int = 1, n_max: int = 2 ** 31 - 1) -> None:
+    """From now on attn_fwd launches this loaded kernel for the shape class it was loaded for."""
+    rc = lib().attn_deploy_codeobj(int(handle), int(n_min), int(n_max))
+    if rc != ATTN_OK:
+        raise AttnError(rc, f"attn_deploy_codeobj({handle})")
+
+
+def attn_deploy_clear() -> None:
+    rc = lib().attn_deploy_clear()
+    if rc != ATTN_OK:
+        raise AttnError(rc, "attn_deploy_clear")
+
+
+def attn_deployed(N: int, d: int, dtype: int, causal: bool):
+    """(matched, variant_id, handle): what attn_fwd launches for this shape; handle is -1
+    unless a deployed code object matches, matched is False when the library default applies."""
+    v, h = ctypes.c_int(-1), ctypes.c_int(-1)
+    rc = lib().attn_deployed(int(N), int(d), int(dtype), int(bool(causal)), ctypes.byref(v), ctypes.byref(h))
+    if rc < 0:
+        raise AttnError(rc, "attn_deployed")
+    return bool(rc), v.value, h.value
 
 
 def attn_fwd_codeobj(handle: int, q, k, v, out, lse, causal: bool, scale: float, stream=None) -> None:

@@ -484,10 +484,92 @@ int attn_fwd_variant(const void* q, const void* k, const void* v, void* out, flo
     return launch(q, k, v, out, lse, B, H, N, d, causal, scale, dtype, stream, variant_id);
 }
 
+// ---- deployed schedules (Sec. 4.1): what attn_fwd launches instead of the default, by shape
+// class.  A small fixed table searched newest first; handle >= 0 names a loaded code object.
+struct Deployment {
+    bool used = false;
+    int variant_id = -1, handle = -1, d = 0, dtype = 0, causal = 0, n_min = 0, n_max = 0;
+};
+constexpr int kMaxDeployed = 16;
+static Deployment g_deployed[kMaxDeployed];
+static int g_num_deployed = 0;
+
+static const Deployment* deployed_for(int N, int d, int dtype, int causal) {
+    for (int i = g_num_deployed - 1; i >= 0; --i) {
+        const Deployment& e = g_deployed[i];
+        if (e.used && e.d == d && e.dtype == dtype && e.causal == (causal ? 1 : 0) && N >= e.n_min && N <= e.n_max) return &e;
+    }
+    return nullptr;
+}
+
+static int add_deployment(const Deployment& e) {
+    if (g_num_deployed == kMaxDeployed) {  // reuse the room of removed entries, keeping the order
+        int n = 0;
+        for (int i = 0; i < kMaxDeployed; ++i)
+            if (g_deployed[i].used) g_deployed[n++] = g_deployed[i];
+        for (int i = n; i < kMaxDeployed; ++i) g_deployed[i] = Deployment();
+        g_num_deployed = n;
+        if (n == kMaxDeployed) return ATTN_EUNSUPPORTED;
+    }
+    g_deployed[g_num_deployed++] = e;
+    return ATTN_OK;
+}
+
 int attn_fwd(const void* q, const void* k, const void* v, void* out, float* lse, int B, int H, int N,
              int d, int causal, float scale, int dtype, void* stream) {
+    if (g_num_deployed > 0) {
+        if (const Deployment* e = deployed_for(N, d, dtype, causal)) {
+            const int rc = launch(q, k, v, out, lse, B, H, N, d, causal, scale, dtype, stream, e->variant_id,
+                                  e->handle >= 0 ? g_loaded[e->handle].fn : nullptr);
+            if (rc != ATTN_EUNSUPPORTED) return rc;
+        }
+    }
     return launch(q, k, v, out, lse, B, H, N, d, causal, scale, dtype, stream,
                   attn_default_variant(N, d, dtype, causal));
+}
+
+int attn_deploy_variant(int variant_id, int d, int dtype, int causal, int n_min, int n_max) {
+    if (variant_id < 0 || variant_id >= kNumVariants || n_min < 1 || n_max < n_min) return ATTN_EINVAL;
+    if ((d != 64 && d != 128) || (dtype != ATTN_F16 && dtype != ATTN_BF16)) return ATTN_EINVAL;
+    if (!kVariants[variant_id].fn[d == 128][dtype][causal ? 1 : 0]) return ATTN_EUNSUPPORTED;
+    Deployment e;
+    e.used = true;
+    e.variant_id = variant_id;
+    e.d = d;
+    e.dtype = dtype;
+    e.causal = causal ? 1 : 0;
+    e.n_min = n_min;
+    e.n_max = n_max;
+    return add_deployment(e);
+}
+
+int attn_deploy_codeobj(int handle, int n_min, int n_max) {
+    if (handle < 0 || handle >= kMaxLoaded || !g_loaded[handle].fn || n_min < 1 || n_max < n_min) return ATTN_EINVAL;
+    const LoadedKernel& lk = g_loaded[handle];
+    Deployment e;
+    e.used = true;
+    e.variant_id = lk.variant_id;
+    e.handle = handle;
+    e.d = lk.d;
+    e.dtype = lk.dtype;
+    e.causal = lk.causal;
+    e.n_min = n_min;
+    e.n_max = n_max;
+    return add_deployment(e);
+}
+
+int attn_deploy_clear(void) {
+    for (int i = 0; i < kMaxDeployed; ++i) g_deployed[i] = Deployment();
+    g_num_deployed = 0;
+    return ATTN_OK;
+}
+
+int attn_deployed(int N, int d, int dtype, int causal, int* variant_id, int* handle) {
+    if (N < 1 || (d != 64 && d != 128) || (dtype != ATTN_F16 && dtype != ATTN_BF16)) return ATTN_EINVAL;
+    const Deployment* e = deployed_for(N, d, dtype, causal);
+    if (variant_id) *variant_id = e ? e->variant_id : attn_default_variant(N, d, dtype, causal);
+    if (handle) *handle = e ? e->handle : -1;
+    return e ? 1 : 0;
 }
 
 int attn_time_variant(const void* q, const void* k, const void* v, void* out, float* lse, int B, int H,
@@ -530,6 +612,8 @@ int attn_codeobj_load(const char* path, const char* kernel_name, int variant_id,
 
 int attn_codeobj_unload(int handle) {
     if (handle < 0 || handle >= kMaxLoaded || !g_loaded[handle].fn) return ATTN_EINVAL;
+    for (int i = 0; i < kMaxDeployed; ++i)  // attn_fwd must not launch a kernel that is gone
+        if (g_deployed[i].used && g_deployed[i].handle == handle) g_deployed[i] = Deployment();
     const hipError_t e = hipModuleUnload(g_loaded[handle].module);
     g_loaded[handle] = LoadedKernel();
     return e == hipSuccess ? ATTN_OK : ATTN_ELAUNCH;

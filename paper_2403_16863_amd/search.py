@@ -449,7 +449,9 @@ def search_workload(widx: int, seed: int = 0, t_max: float = 0.05, t_min: float 
         os.makedirs(STORE_DIR, exist_ok=True)
         rounds.append({"seed": seed, "start_variant": start, "steps": len(res.steps), "visited": len(res.times),
                        "best_of_round": lat.points[res.best]})
-        summary = {"workload": w.label, "measured_on": torch.cuda.get_device_name(0), "rounds": rounds,
+        summary = {"workload": w.label,
+                   "shape": {"B": w.B, "H": w.H, "N": w.N, "d": w.d, "causal": bool(w.causal), "dtype": int(w.dtype)},
+                   "measured_on": torch.cuda.get_device_name(0), "rounds": rounds,
                    "admission_samples": samples, "default_variant": default, "best_variant": best_v,
                    "best_desc": Bd.attn_variant_desc(best_v), "best_vs_default": report["validated"]["best_vs_default"],
                    "best_vs_variant0": report["validated"]["best_vs_variant0"],

@@ -495,6 +495,13 @@ class GpuRunner:
             self._handles[key] = self.B.attn_codeobj_load(co, self.kernel.name, self.variant, self.w.d, self.w.dtype, self.w.causal)
         return self._handles[key]
 
+    def close(self) -> None:
+        """Unloads every candidate still held (the library's handle table is process-wide)."""
+        self.torch.cuda.synchronize()
+        for h in self._handles.values():
+            self.B.attn_codeobj_unload(h)
+        self._handles.clear()
+
     def admit(self, s: Schedule) -> bool:
         """Probabilistic test of Sec. 4.2 against the unmodified kernel (the variant's own).  A
         re-ordered copy performs the same floating-point operations in the same order, so its
@@ -528,14 +535,19 @@ class GpuRunner:
 
 def search_workload(widx: int, seed: int = 0, t_max: float = 0.05, t_min: float = 5e-4, cool: float = 1.05,
                     samples: int = 64, variant: Optional[int] = None, db_path: Optional[str] = None,
-                    keep_best: Optional[str] = None, verbose: bool = False, validate_rounds: int = 7) -> dict:
-    """Simulated annealing (Alg. 1) over instruction positions of the kernel a workload uses."""
+                    keep_best: Optional[str] = None, verbose: bool = False, validate_rounds: int = 7,
+                    keep_codeobj: Optional[str] = None) -> dict:
+    """Simulated annealing (Alg. 1) over instruction positions of the kernel a workload uses.
+    keep_best: file for the winner's assembly; keep_codeobj: file for its code object (with a
+    .json description next to it), which `deploy.deploy_codeobj_file` can make the kernel that
+    attn_fwd launches (Sec. 4.1)."""
     from . import binding as B
     from . import inputs as I
     from .search import anneal_states
     w = I.WORKLOADS[widx]
     variant = B.attn_default_variant(w.N, w.d, w.dtype, w.causal) if variant is None else variant
     workdir = tempfile.mkdtemp(prefix="sip_")
+    run = None
     try:
         kernel = Kernel(compile_base(workdir, w.d, w.dtype, w.causal, knobs_of_variant(variant)))
         x0 = Schedule(tuple(kernel.nodes))
@@ -570,6 +582,10 @@ def search_workload(widx: int, seed: int = 0, t_max: float = 0.05, t_min: float 
         if keep_best:
             with open(keep_best, "w") as f:
                 f.write(kernel.render(list(best.nodes)))
+        if keep_codeobj:
+            from .deploy import save_codeobj
+            save_codeobj(assemble(kernel.render(list(best.nodes)), workdir, "kept"), keep_codeobj, kernel.name, variant, w,
+                         statistics.median(again0) / statistics.median(again1) if again0 else None)
         return {
             "workload": w.label, "seed": seed, "variant": variant, "variant_desc": B.attn_variant_desc(variant),
             "movable_instructions": len(movable_positions(kernel.nodes)), "steps": len(res.steps),
@@ -583,6 +599,8 @@ def search_workload(widx: int, seed: int = 0, t_max: float = 0.05, t_min: float 
             "paper_context": "A100 speed-ups reported by the paper: 1.062x (attention), 1.123x (GEMM+LeakyReLU)",
         }
     finally:
+        if run is not None:
+            run.close()
         shutil.rmtree(workdir, ignore_errors=True)
 
 
@@ -635,6 +653,13 @@ class GemmRunner:
             self._handles[key] = self.G.gemm_lrelu_codeobj_load(co, self.kernel.name, self.variant, self.dtype)
         return self._handles[key]
 
+    def close(self) -> None:
+        """Unloads every candidate still held (the library's handle table is process-wide)."""
+        self.torch.cuda.synchronize()
+        for h in self._handles.values():
+            self.G.gemm_lrelu_codeobj_unload(h)
+        self._handles.clear()
+
     def admit(self, s: Schedule) -> bool:
         """A reordered kernel performs the same fp32 operations in the same order per element, so
         its output must equal the unmodified kernel's bit for bit, on every shape and family."""
@@ -670,6 +695,7 @@ def search_gemm(seed: int = 0, t_max: float = 0.05, t_min: float = 5e-4, cool: f
     from .search import anneal_states
     variant = G.gemm_lrelu_default_variant(I.GEMM_M, I.GEMM_N, I.GEMM_K) if variant is None else variant
     workdir = tempfile.mkdtemp(prefix="sip_gemm_")
+    run = None
     try:
         kernel = Kernel(compile_gemm_base(workdir, dtype, G.gemm_lrelu_variant_knobs(variant)), loop_depth=1)
         x0 = Schedule(tuple(kernel.nodes))
@@ -709,6 +735,8 @@ def search_gemm(seed: int = 0, t_max: float = 0.05, t_min: float = 5e-4, cool: f
             "paper_context": "A100 speed-up reported by the paper for this workload: 1.123x (23.97 vs 26.91 us)",
         }
     finally:
+        if run is not None:
+            run.close()
         shutil.rmtree(workdir, ignore_errors=True)
 
 
@@ -724,13 +752,15 @@ def main(argv: Optional[Sequence[str]] = None) -> None:
     ap.add_argument("--samples", type=int, default=64, help="random inputs per admission test")
     ap.add_argument("--db", type=str, default=None, help="append every step as JSON lines to this file")
     ap.add_argument("--keep-best", type=str, default=None, help="write the best kernel's assembly to this file")
+    ap.add_argument("--keep-codeobj", type=str, default=None,
+                    help="write the best kernel's code object (and FILE.json) for deploy.deploy_codeobj_file")
     ap.add_argument("--verbose", action="store_true")
     a = ap.parse_args(argv)
     if a.gemm:
         print(json.dumps(search_gemm(a.seed, a.tmax, a.tmin, a.cool, min(a.samples, 12), a.variant, 0, a.keep_best, a.verbose)))
         return
     print(json.dumps(search_workload(a.workload, a.seed, a.tmax, a.tmin, a.cool, a.samples, a.variant, a.db,
-                                     a.keep_best, a.verbose)))
+                                     a.keep_best, a.verbose, keep_codeobj=a.keep_codeobj)))
 
 
 if __name__ == "__main__":

@@ -52,3 +52,51 @@ def test_product_admission_accepts_every_built_variant():
             if A.attn_variant_supported(var, d, dtype, causal):
                 print(f"admit variant {var} d={d} dtype={dtype} causal={causal}", flush=True)
                 assert S.admit_against_default(var, d, dtype, causal, samples=48, seed=1)
+
+
+def test_a_deployed_variant_is_what_attn_fwd_launches():
+    """Sec. 4.1: after deployment attn_fwd runs the searched schedule for its shape class and
+    range, and the library default everywhere else; every result still matches the oracle."""
+    import torch
+    import paper_2403_16863_amd as A
+    from gpu_util import to_device
+    w = I.Workload("dep", 1, 3, 1000, 128, True, I.BF16)
+    qb, kb, vb = I.make_qkv(w, seed=77)
+    q, k, v = (to_device(a, w.dtype) for a in (qb, kb, vb))
+    O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, True, w.scale, w.dtype)
+    default = A.attn_default_variant(w.N, w.d, w.dtype, True)
+
+    def run(fn):
+        o = torch.full_like(q, float("nan"))
+        l = torch.full(q.shape[:3], float("nan"), dtype=torch.float32, device="cuda")
+        fn(o, l)
+        torch.cuda.synchronize()
+        return o, l
+
+    o_def, l_def = run(lambda o, l: A.attn_fwd_variant(q, k, v, o, l, True, w.scale, default))
+    # a schedule whose output differs from the default's in some bit (another tile size sums in
+    # another order), or the comparisons below would show nothing
+    for other in range(A.attn_num_variants()):
+        if other == default or A.attn_variant_supported(other, w.d, w.dtype, True) != 1:
+            continue
+        o_other, l_other = run(lambda o, l: A.attn_fwd_variant(q, k, v, o, l, True, w.scale, other))
+        if not torch.equal(o_other.view(torch.int16), o_def.view(torch.int16)):
+            break
+    else:
+        pytest.fail("every variant is bit-identical to the default on this input")
+    try:
+        A.attn_deploy_variant(other, w.d, w.dtype, True, 512, 2048)
+        assert A.attn_deployed(w.N, w.d, w.dtype, True) == (True, other, -1)
+        o, l = run(lambda o, l: A.attn_fwd(q, k, v, o, l, True, w.scale))
+        assert torch.equal(o.view(torch.int16), o_other.view(torch.int16)) and torch.equal(l, l_other)
+        check(o.double().cpu().numpy(), l.double().cpu().numpy(), O_ref, l_ref, w.dtype, what="deployed variant")
+        # outside the range (and for another mask) the default runs
+        A.attn_deploy_clear()
+        A.attn_deploy_variant(other, w.d, w.dtype, True, 2000, 4000)
+        A.attn_deploy_variant(other, w.d, w.dtype, False, 1, 100000)
+        o, l = run(lambda o, l: A.attn_fwd(q, k, v, o, l, True, w.scale))
+        assert torch.equal(o.view(torch.int16), o_def.view(torch.int16)) and torch.equal(l, l_def)
+    finally:
+        A.attn_deploy_clear()
+    o, l = run(lambda o, l: A.attn_fwd(q, k, v, o, l, True, w.scale))
+    assert torch.equal(o.view(torch.int16), o_def.view(torch.int16))

@@ -60,7 +60,8 @@ def test_short_search_winner_passes_the_oracle():
     d = tempfile.mkdtemp(prefix="sip_gpu_")
     try:
         # ~14 annealing steps on the bench workload, then the winner on a ragged causal shape vs the oracle
-        out = sip.search_workload(2, seed=3, t_max=0.05, t_min=0.025, cool=1.05, samples=8, keep_best=d + "/best.s")
+        out = sip.search_workload(2, seed=3, t_max=0.05, t_min=0.025, cool=1.05, samples=8, keep_best=d + "/best.s",
+                                  keep_codeobj=d + "/best.co")
         assert out["steps"] >= 10 and out["admitted"] >= 1
         assert out["best_ms"] <= out["unmodified_codeobj_ms"]
         variant = out["variant"]
@@ -77,6 +78,26 @@ def test_short_search_winner_passes_the_oracle():
         O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, True, w.scale, w.dtype)
         check(o.to(torch.float64).cpu().numpy(), l.to(torch.float64).cpu().numpy(), O_ref, l_ref, w.dtype, what="search winner")
         A.attn_codeobj_unload(h)
+        # Sec. 4.1: the kept code object, deployed, is what attn_fwd launches for its shape class,
+        # until it is unloaded
+        from paper_2403_16863_amd import deploy
+        try:
+            h2 = deploy.deploy_codeobj_file(d + "/best.co", 1, 100000)
+            assert A.attn_deployed(1000, 128, A.ATTN_BF16, True) == (True, variant, h2)
+            assert not A.attn_deployed(1000, 128, A.ATTN_BF16, False)[0]
+            o2 = torch.full_like(q, float("nan"))
+            l2 = torch.full_like(l, float("nan"))
+            A.attn_fwd(q, kk, v, o2, l2, True, w.scale)
+            torch.cuda.synchronize()
+            assert torch.equal(o2.view(torch.int16), o.view(torch.int16)) and torch.equal(l2, l)
+            A.attn_codeobj_unload(h2)
+            assert not A.attn_deployed(1000, 128, A.ATTN_BF16, True)[0]
+            o2.fill_(float("nan"))
+            A.attn_fwd(q, kk, v, o2, l2, True, w.scale)       # the library's own kernel again
+            torch.cuda.synchronize()
+            check(o2.to(torch.float64).cpu().numpy(), l2.to(torch.float64).cpu().numpy(), O_ref, l_ref, w.dtype, what="after unload")
+        finally:
+            A.attn_deploy_clear()
     finally:
         shutil.rmtree(d, ignore_errors=True)
 
