@@ -210,7 +210,13 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
     constexpr int NVF = KT * 2 * DT;  // V fragments (MFMA steps of the second contraction) per tile
     constexpr int NKF = KS * KT;      // K fragments (MFMA steps of the first contraction) per tile
 
-    __shared__ __attribute__((aligned(256))) u32x4 smem[2 * NB * TILE_CHUNKS];  // K0 V0 K1 V1 (K2 V2)
+    // The ping-pong order with tiles straight to LDS also brings Q in through LDS: the B-operand
+    // layout wants 32 bytes of each of 32 rows per load instruction, which the texture path
+    // takes as 32 separate requests (a workgroup's 64 KB of Q then cost more than all its first
+    // tiles together); whole rows, 1 KB per wave instruction, land in a staging area laid out
+    // like a K tile of BM rows, and each wave reads its fragments from there.
+    constexpr bool QSTAGE = PIPE == 1 && LDP == 1;
+    __shared__ __attribute__((aligned(256))) u32x4 smem[2 * NB * TILE_CHUNKS + (QSTAGE ? BM * CPR : 0)];  // K0 V0 K1 V1, Q
     char* const smem_b = reinterpret_cast<char*>(smem);
 
     const int tid = threadIdx.x;
@@ -365,6 +371,36 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
             if (whole) pieces(std::true_type{});
             else pieces(std::false_type{});
         };
+        // Q through LDS (QSTAGE): the BM rows of the query tile move like a K tile of BM rows
+        // (piece i = rows i * NT / CPR onward, rows past the end of the sequence redirected to the
+        // last row: those queries are never stored), and wave w finds row c, chunk 2 ks + g of its
+        // 32 rows at the K read offset of the same (c, ks, g), 32 w rows further on.
+        auto request_q = [&]() __attribute__((always_inline)) {
+            constexpr std::integral_constant<int, NT> nt_c{};
+            const bool whole = q0 + BM <= N;
+            u32x4 unused;
+            auto pieces = [&](auto whole_c) __attribute__((always_inline)) {
+#pragma unroll
+                for (int i = 0; i < BM * CPR / NT; ++i)
+                    issue_piece(nt_c, decltype(whole_c)::value, reinterpret_cast<const char*>(Qh), goffK0, wave, q0,
+                                smem_b + 2 * NB * TILE_BYTES, i, unused);
+            };
+            if (whole) pieces(std::true_type{});
+            else pieces(std::false_type{});
+        };
+        auto read_q = [&]() __attribute__((always_inline)) {
+            static_assert(QB == 1 || !QSTAGE, "one 32-row block per wave");
+            // (the offset is made opaque here: otherwise the compiler forms the eight addresses
+            // once, ahead of the item loop, and spills them)
+            int mine = 2 * NB * TILE_BYTES + wave * (32 * RB);
+            asm volatile("" : "+s"(mine));
+            const unsigned flip = p.qmode == 1 ? 0x80008000u : 0u, keep = p.qmode == 2 ? 0u : 0xffffffffu;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const u32x4 val = *reinterpret_cast<const u32x4*>(smem_b + mine + koff[ks]);
+                qreg[0][ks] = (val ^ flip) & keep;  // q' = -q flips the sign of all eight elements, q' = 0 clears them
+            }
+        };
         auto issue_k = [&](int j, int buf) __attribute__((always_inline)) { issue_tiles(j, buf, -1, 0); };
         auto issue_v = [&](int j, int buf) __attribute__((always_inline)) { issue_tiles(-1, 0, j, buf); };
         // make the tiles issued last visible in LDS to this thread (K into buffer kbuf, V into vbuf)
@@ -472,6 +508,37 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
                 constexpr int qb = decltype(qb_c)::value;
                 const float mb = m_use[qb] * p.scale_l2;
                 float rs0 = 0.f, rs1 = 0.f;  // row sum of the unrounded probabilities, fp32
+                if constexpr (PIPE == 1) {
+                    // The V cluster is one wave's vector instructions, back to back, and the order matters:
+                    // two exponentials close together meet in the transcendental pipe and the second one
+                    // waits (7 % of the tile loop between the orders the compiler picks from one build to
+                    // the next).  So the order is pinned: a three-stage pipeline over the pairs in which
+                    // every exponential is followed by the multiply-add of the next pair, a row-sum
+                    // addition and, every other time, the conversion of the pair before.
+                    float xa = 0.f, xb = 0.f, ea = 0.f, eb = 0.f;
+                    static_for<KT * 8 + 2>([&](auto i_c) __attribute__((always_inline)) {
+                        constexpr int i = decltype(i_c)::value;  // step: pair i enters, pair i-1 in exp, pair i-2 leaves
+                        constexpr bool IN = i < KT * 8, MID = i >= 1 && i <= KT * 8, OUT = i >= 2;
+                        constexpr int kt = (IN ? i : 0) / 8, t = ((IN ? i : 0) / 4) % 2, h = (IN ? i : 0) % 4;
+                        constexpr int j = OUT ? i - 2 : 0, jkt = j / 8, jt = (j / 4) % 2, jh = j % 4;
+                        float na = 0.f, nb = 0.f, fa = 0.f, fb = 0.f;
+                        if constexpr (MID) { fa = __builtin_amdgcn_exp2f(xa); __builtin_amdgcn_sched_barrier(0); }
+                        if constexpr (IN) { na = __builtin_fmaf(s[qb][kt][8 * t + 2 * h], p.scale_l2, -mb); __builtin_amdgcn_sched_barrier(0); }
+                        if constexpr (OUT) { rs0 += ea; __builtin_amdgcn_sched_barrier(0); }
+                        if constexpr (OUT) {
+                            unsigned packed = T::pack2(ea, eb);
+                            asm volatile("" : "+v"(packed));
+                            pk[qb][jkt][jt][jh] = packed;
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        if constexpr (MID) { fb = __builtin_amdgcn_exp2f(xb); __builtin_amdgcn_sched_barrier(0); }
+                        if constexpr (IN) { nb = __builtin_fmaf(s[qb][kt][8 * t + 2 * h + 1], p.scale_l2, -mb); __builtin_amdgcn_sched_barrier(0); }
+                        if constexpr (OUT) { rs1 += eb; __builtin_amdgcn_sched_barrier(0); }
+                        xa = na; xb = nb; ea = fa; eb = fb;
+                    });
+                    rs[qb] = rs0 + rs1;
+                    return;
+                }
                 static_for<KT * 2>([&](auto kk_c) __attribute__((always_inline)) {
                     constexpr int kt = decltype(kk_c)::value / 2, t = decltype(kk_c)::value % 2;
                     u32x4 w;
@@ -986,7 +1053,11 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
 
             issue_k(0, 0);
             issue_v(0, 0);
-            if constexpr (LDP == 1) {
+            if constexpr (QSTAGE) {
+                issue_k(1, 1);  // all three first tiles in flight together, one wait
+                request_q();
+                land_loads(0, 0);
+            } else if constexpr (LDP == 1) {
                 issue_k(1, 1);  // all three first tiles in flight together, one wait
                 load_q();
                 land_loads(0, 0);
@@ -998,6 +1069,7 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
                 land_loads(1, 1);
             }
             __syncthreads();
+            if constexpr (QSTAGE) read_q();
             mfma_stream(no, yes, c0, c0, pk, s);
             softmax_first_tile(s, pk);
             __syncthreads();  // every wave has read K(0) before K(2) overwrites it
