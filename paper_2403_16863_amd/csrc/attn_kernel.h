@@ -215,7 +215,9 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
     // takes as 32 separate requests (a workgroup's 64 KB of Q then cost more than all its first
     // tiles together); whole rows, 1 KB per wave instruction, land in a staging area laid out
     // like a K tile of BM rows, and each wave reads its fragments from there.
-    constexpr bool QSTAGE = PIPE == 1 && LDP == 1;
+    // (Also for the free-running order at d = 64, where the staging area fits next to the tiles
+    // of three workgroups per compute unit; at d = 128 two such workgroups would need 192 KB.)
+    constexpr bool QSTAGE = LDP == 1 && QB == 1 && (PIPE == 1 || (PIPE == 0 && D == 64));
     __shared__ __attribute__((aligned(256))) u32x4 smem[2 * NB * TILE_CHUNKS + (QSTAGE ? BM * CPR : 0)];  // K0 V0 K1 V1, Q
     char* const smem_b = reinterpret_cast<char*>(smem);
 
@@ -706,9 +708,11 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
             };
             issue_k(0, 0);
             issue_v(0, 0);
-            load_q();
+            if constexpr (QSTAGE) request_q();
+            else load_q();
             land_loads(0, 0);
             __syncthreads();
+            if constexpr (QSTAGE) read_q();
             for (int j = 0; j < nkt; j += 2) {
                 step(c0, j);
                 if (j + 1 < nkt) step(c1, j + 1);
