@@ -191,12 +191,17 @@ def test_scale_argument_and_stream():
     import torch
     import paper_2403_16863_amd as A
     from gpu_util import to_device
+    # (a zero and a negative scale take their own paths where Q enters the registers: q' = 0, q' = -q;
+    # both the staged and the direct form of that are covered: d = 128 ping-pong, d = 64, and variant 0)
+    for w2, variant in ((I.Workload("t", 1, 2, 300, 64, True, I.F16), None), (I.Workload("t", 1, 2, 300, 128, True, I.BF16), None),
+                        (I.Workload("t", 2, 1, 200, 128, False, I.BF16), 0)):
+        qb, kb, vb = I.make_qkv(w2, seed=5)
+        for scale in (0.0, 0.03, 0.5, -0.2):
+            O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, w2.causal, float(np.float32(scale)), w2.dtype)
+            O, l = run_gpu(qb, kb, vb, w2.causal, scale, w2.dtype, variant=variant)
+            check(O, l, O_ref, l_ref, w2.dtype, what=f"scale={scale} d={w2.d} variant={variant}")
     w = I.Workload("t", 1, 2, 300, 64, True, I.F16)
     qb, kb, vb = I.make_qkv(w, seed=5)
-    for scale in (0.0, 0.03, 0.5, -0.2):
-        O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, True, float(np.float32(scale)), I.F16)
-        O, l = run_gpu(qb, kb, vb, True, scale, I.F16)
-        check(O, l, O_ref, l_ref, I.F16, what=f"scale={scale}")
     s = torch.cuda.Stream()
     q, k, v = (to_device(a, I.F16) for a in (qb, kb, vb))
     out = torch.empty_like(q)
