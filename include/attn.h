@@ -26,7 +26,8 @@
  *  - every pointer named "device" is a HIP device pointer owned by the caller;
  *    the library allocates no device memory and frees none.  Its only mutable state
  *    is process-wide and small: the compute-unit count of each device, read once,
- *    and the table of loaded code objects (attn_codeobj_*), which is not synchronised;
+ *    and the tables of loaded code objects and deployed schedules (attn_codeobj_*,
+ *    attn_deploy_*), which are not synchronised;
  *  - calls are asynchronous: work is enqueued on `stream` (a hipStream_t passed
  *    as void*, NULL = the default stream) and the call returns without waiting;
  *  - the return value is ATTN_OK or a negative error code; on error nothing has

@@ -28,7 +28,10 @@ struct Variant {
 // each); dense = 1 asks for one workgroup more than that (three waves per SIMD: their vector
 // instructions fill the issue slots a single wave leaves empty; d = 64 only, where the registers
 // allow it).  ilv = how MFMA, LDS-read, transcendental and other vector instructions are grouped
-// in the interleaved order (sched_group_barrier patterns); ldpos = where in that order's stream a
+// in the interleaved order (sched_group_barrier patterns), and for the ping-pong order the order of
+// the softmax's vector instructions (0: every exponential followed by a multiply-add, an addition
+// and every other time a conversion, pinned; 1: exponentials in pairs, pinned; 2: the compiler's
+// own order); ldpos = where in the interleaved order's stream a
 // wave issues its tile loads (all after the barrier, after fixed MFMA slots, after slots that
 // depend on the wave): the position of the memory instructions, which is what Sec. 3.1 perturbs.
 const char* const kKnobNames[] = {"bn", "nw", "qb", "ldp", "pipe", "pf", "prio", "dense", "ilv", "ldpos"};
@@ -71,6 +74,11 @@ constexpr int kNumKnobs = 10;
     {VARIANT_HEAD(64, 8, 1, 1, LDP, 3, PF, PRIO, ILV, LDPOS),                                       \
      {ATTN_NO_KERNELS, ATTN_KERNELS_FOR(128, 64, 8, 1, 1, LDP, 3, PF, PRIO, ILV, LDPOS)}}
 
+// the ping-pong order of variant 11 with another order of the V cluster's vector instructions (d = 128)
+#define VARIANT_PP_ILV(ILV)                                                                         \
+    {VARIANT_HEAD(64, 8, 1, 1, 1, 1, 4, 1, ILV, 0),                                                 \
+     {ATTN_NO_KERNELS, ATTN_KERNELS_FOR(128, 64, 8, 1, 1, 1, 1, 4, 1, ILV, 0)}}
+
 const Variant kVariants[] = {
     VARIANT_BOTH(64, 4, 1, 2, 1, 0, 4, 0),   // 0: the hand-written default
     VARIANT_BOTH(64, 4, 1, 2, 1, 0, 2, 0),
@@ -105,6 +113,8 @@ const Variant kVariants[] = {
     VARIANT_ILV(1, 4, 0, 0, 0),              // 30 .. 32: the interleaved order, tiles straight to LDS
     VARIANT_ILV(1, 4, 0, 0, 1),
     VARIANT_ILV(1, 4, 1, 0, 0),              // (one knob away from variant 16: the lattice stays connected)
+    VARIANT_PP_ILV(1),                       // 33, 34: the default ping-pong kernel with the other orders of the softmax
+    VARIANT_PP_ILV(2),                       //         instructions (exponentials in pairs; the compiler's own order)
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
