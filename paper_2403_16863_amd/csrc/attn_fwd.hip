@@ -30,8 +30,8 @@ struct Variant {
 // allow it).  ilv = how MFMA, LDS-read, transcendental and other vector instructions are grouped
 // in the interleaved order (sched_group_barrier patterns), and for the ping-pong order the order of
 // the softmax's vector instructions (0: every exponential followed by a multiply-add, an addition
-// and every other time a conversion, pinned; 1: exponentials in pairs, pinned; 2: the compiler's
-// own order); ldpos = where in the interleaved order's stream a
+// and every other time a conversion, pinned; 1: multiply-adds and exponentials alternating, then the
+// sums and the conversion, pinned; 2: the compiler's own order); ldpos = where in the interleaved order's stream a
 // wave issues its tile loads (all after the barrier, after fixed MFMA slots, after slots that
 // depend on the wave): the position of the memory instructions, which is what Sec. 3.1 perturbs.
 const char* const kKnobNames[] = {"bn", "nw", "qb", "ldp", "pipe", "pf", "prio", "dense", "ilv", "ldpos"};
@@ -114,7 +114,7 @@ const Variant kVariants[] = {
     VARIANT_ILV(1, 4, 0, 0, 1),
     VARIANT_ILV(1, 4, 1, 0, 0),              // (one knob away from variant 16: the lattice stays connected)
     VARIANT_PP_ILV(1),                       // 33, 34: the default ping-pong kernel with the other orders of the softmax
-    VARIANT_PP_ILV(2),                       //         instructions (exponentials in pairs; the compiler's own order)
+    VARIANT_PP_ILV(2),                       //         instructions (a second pinned order; the compiler's own order)
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 

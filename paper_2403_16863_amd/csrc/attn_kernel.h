@@ -511,15 +511,16 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
                 const float mb = m_use[qb] * p.scale_l2;
                 float rs0 = 0.f, rs1 = 0.f;  // row sum of the unrounded probabilities, fp32
                 if constexpr (PIPE == 1 && ILV != 2) {
-                    // The V cluster is one wave's vector instructions, back to back, and the order matters:
-                    // two exponentials close together meet in the transcendental pipe and the second one
-                    // waits (7 % of the tile loop between the orders the compiler picks from one build to
-                    // the next).  So the order is pinned: a three-stage pipeline over the pairs in which
-                    // every exponential is followed by the multiply-add of the next pair, a row-sum
-                    // addition and, every other time, the conversion of the pair before (ILV 0).
-                    // The knob's other points, for the search to compare: ILV 1 pins the opposite
-                    // grouping (both exponentials of a pair, then both multiply-adds, then the sums),
-                    // ILV 2 leaves the order to the compiler.
+                    // The V cluster is one wave's vector instructions, back to back.  Left to the compiler
+                    // their order comes out differently from one build to the next (an unrelated edit
+                    // elsewhere in the kernel is enough), and the builds fall into two groups 5 to 7 % of
+                    // the tile loop apart.  Pinned in the source, as a three-stage pipeline over the pairs
+                    // (multiply-adds of pair i+1, exponentials of pair i, sums and conversion of pair
+                    // i-1, the conversion kept next to its pair instead of sinking behind the slow-path
+                    // test), every order tried lands in the fast group.  ILV 0: exponential, multiply-add,
+                    // sum, conversion, exponential, multiply-add, sum; ILV 1: multiply-add, exponential,
+                    // multiply-add, exponential, sum, conversion, sum; ILV 2 leaves the order to the
+                    // compiler (a lattice point for the search to compare).
                     float xa = 0.f, xb = 0.f, ea = 0.f, eb = 0.f;
                     static_for<KT * 8 + 2>([&](auto i_c) __attribute__((always_inline)) {
                         constexpr int i = decltype(i_c)::value;  // step: pair i enters, pair i-1 in exp, pair i-2 leaves
@@ -527,21 +528,22 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
                         constexpr int kt = (IN ? i : 0) / 8, t = ((IN ? i : 0) / 4) % 2, h = (IN ? i : 0) % 4;
                         constexpr int j = OUT ? i - 2 : 0, jkt = j / 8, jt = (j / 4) % 2, jh = j % 4;
                         float na = 0.f, nb = 0.f, fa = 0.f, fb = 0.f;
-                        if constexpr (MID) { fa = __builtin_amdgcn_exp2f(xa); __builtin_amdgcn_sched_barrier(0); }
-                        if constexpr (ILV == 1 && MID) { fb = __builtin_amdgcn_exp2f(xb); __builtin_amdgcn_sched_barrier(0); }
-                        if constexpr (IN) { na = __builtin_fmaf(s[qb][kt][8 * t + 2 * h], p.scale_l2, -mb); __builtin_amdgcn_sched_barrier(0); }
-                        if constexpr (ILV == 1 && IN) { nb = __builtin_fmaf(s[qb][kt][8 * t + 2 * h + 1], p.scale_l2, -mb); __builtin_amdgcn_sched_barrier(0); }
-                        if constexpr (OUT) { rs0 += ea; __builtin_amdgcn_sched_barrier(0); }
-                        if constexpr (ILV == 1 && OUT) { rs1 += eb; __builtin_amdgcn_sched_barrier(0); }
-                        if constexpr (OUT) {
-                            unsigned packed = T::pack2(ea, eb);
-                            asm volatile("" : "+v"(packed));
-                            pk[qb][jkt][jt][jh] = packed;
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                        if constexpr (ILV != 1 && MID) { fb = __builtin_amdgcn_exp2f(xb); __builtin_amdgcn_sched_barrier(0); }
-                        if constexpr (ILV != 1 && IN) { nb = __builtin_fmaf(s[qb][kt][8 * t + 2 * h + 1], p.scale_l2, -mb); __builtin_amdgcn_sched_barrier(0); }
-                        if constexpr (ILV != 1 && OUT) { rs1 += eb; __builtin_amdgcn_sched_barrier(0); }
+                        auto exp_a = [&]() __attribute__((always_inline)) { if constexpr (MID) { fa = __builtin_amdgcn_exp2f(xa); __builtin_amdgcn_sched_barrier(0); } };
+                        auto exp_b = [&]() __attribute__((always_inline)) { if constexpr (MID) { fb = __builtin_amdgcn_exp2f(xb); __builtin_amdgcn_sched_barrier(0); } };
+                        auto fma_a = [&]() __attribute__((always_inline)) { if constexpr (IN) { na = __builtin_fmaf(s[qb][kt][8 * t + 2 * h], p.scale_l2, -mb); __builtin_amdgcn_sched_barrier(0); } };
+                        auto fma_b = [&]() __attribute__((always_inline)) { if constexpr (IN) { nb = __builtin_fmaf(s[qb][kt][8 * t + 2 * h + 1], p.scale_l2, -mb); __builtin_amdgcn_sched_barrier(0); } };
+                        auto add_a = [&]() __attribute__((always_inline)) { if constexpr (OUT) { rs0 += ea; __builtin_amdgcn_sched_barrier(0); } };
+                        auto add_b = [&]() __attribute__((always_inline)) { if constexpr (OUT) { rs1 += eb; __builtin_amdgcn_sched_barrier(0); } };
+                        auto cvt = [&]() __attribute__((always_inline)) {
+                            if constexpr (OUT) {
+                                unsigned packed = T::pack2(ea, eb);
+                                asm volatile("" : "+v"(packed));
+                                pk[qb][jkt][jt][jh] = packed;
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                        };
+                        if constexpr (ILV == 0) { exp_a(); fma_a(); add_a(); cvt(); exp_b(); fma_b(); add_b(); }
+                        else { fma_a(); exp_a(); fma_b(); exp_b(); add_a(); cvt(); add_b(); }
                         xa = na; xb = nb; ea = fa; eb = fb;
                     });
                     rs[qb] = rs0 + rs1;
