@@ -34,6 +34,8 @@ struct Variant {
 // sums and the conversion, pinned; 2: the compiler's own order); ldpos = where in the interleaved order's stream a
 // wave issues its tile loads (all after the barrier, after fixed MFMA slots, after slots that
 // depend on the wave): the position of the memory instructions, which is what Sec. 3.1 perturbs.
+// On the ping-pong order ldpos 1 moves the tile loads one tile further ahead, into a third pair of
+// buffers, which leaves one workgroup barrier per tile instead of two.
 const char* const kKnobNames[] = {"bn", "nw", "qb", "ldp", "pipe", "pf", "prio", "dense", "ilv", "ldpos"};
 const int kKnobSizes[] = {3, 2, 2, 2, 4, 4, 3, 2, 3, 3};
 constexpr int kNumKnobs = 10;
@@ -79,6 +81,11 @@ constexpr int kNumKnobs = 10;
     {VARIANT_HEAD(64, 8, 1, 1, 1, 1, 4, 1, ILV, 0),                                                 \
      {ATTN_NO_KERNELS, ATTN_KERNELS_FOR(128, 64, 8, 1, 1, 1, 1, 4, 1, ILV, 0)}}
 
+// the ping-pong order with three buffers and one barrier per tile (ldpos 1 on that order; d = 128)
+#define VARIANT_PP_3BUF(PF)                                                                         \
+    {VARIANT_HEAD(64, 8, 1, 1, 1, 1, PF, 1, 0, 1),                                                  \
+     {ATTN_NO_KERNELS, ATTN_KERNELS_FOR(128, 64, 8, 1, 1, 1, 1, PF, 1, 0, 1)}}
+
 const Variant kVariants[] = {
     VARIANT_BOTH(64, 4, 1, 2, 1, 0, 4, 0),   // 0: the hand-written default
     VARIANT_BOTH(64, 4, 1, 2, 1, 0, 2, 0),
@@ -115,6 +122,8 @@ const Variant kVariants[] = {
     VARIANT_ILV(1, 4, 1, 0, 0),              // (one knob away from variant 16: the lattice stays connected)
     VARIANT_PP_ILV(1),                       // 33, 34: the default ping-pong kernel with the other orders of the softmax
     VARIANT_PP_ILV(2),                       //         instructions (a second pinned order; the compiler's own order)
+    VARIANT_PP_3BUF(4),                      // 35, 36: ping-pong with three K/V buffers, loads one tile further ahead,
+    VARIANT_PP_3BUF(2),                      //         one workgroup barrier per tile (pf 4 / 2)
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 

@@ -195,7 +195,11 @@ template <class T, int D, bool CAUSAL, class KN>
 __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Params p) {
     constexpr int BN = KN::BN, NW = KN::NW, QB = KN::QB, LDP = KN::LDP, PIPE = KN::PIPE, PF = KN::PF, PRIO = KN::PRIO;
     constexpr int ILV = KN::ILV, LDPOS = KN::LDPOS;
-    constexpr int NB = 2;            // K buffers and V buffers in LDS
+    // Ping-pong order with LDPOS 1: three K and three V buffers, tile loads one tile further ahead,
+    // ONE workgroup barrier per tile (see there).  Layout then K0 K1 K2 V0 V1 V2, so that the
+    // immediate offsets of the K reads and of the V reads each stay inside their 64 KB.
+    constexpr bool NB3 = PIPE == 1 && LDPOS == 1;
+    constexpr int NB = NB3 ? 3 : 2;  // K buffers and V buffers in LDS
     constexpr int NT = NW * 64;
     constexpr int BM = 32 * QB * NW;
     constexpr int KS = D / 16;       // k-steps of the first contraction
@@ -220,6 +224,10 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
     constexpr bool QSTAGE = LDP == 1 && QB == 1 && (PIPE == 1 || (PIPE == 0 && D == 64));
     __shared__ __attribute__((aligned(256))) u32x4 smem[2 * NB * TILE_CHUNKS + (QSTAGE ? BM * CPR : 0)];  // K0 V0 K1 V1, Q
     char* const smem_b = reinterpret_cast<char*>(smem);
+
+    auto k_off = [](int b) { return NB3 ? b * TILE_BYTES : b * 2 * TILE_BYTES; };                       // K buffer b, bytes from the start of LDS
+    auto v_off = [](int b) { return NB3 ? (NB + b) * TILE_BYTES : b * 2 * TILE_BYTES + TILE_BYTES; };  // V buffer b
+    auto v_rel = [](int b) { return NB3 ? b * TILE_BYTES : b * 2 * TILE_BYTES + TILE_BYTES; };         // the same, from where voff[] counts
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -301,6 +309,12 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
                 const int dcol = dt * 32 + ((lane >> 4) & 1) * 16 + 4 * (i16 & 3);
                 voff[dt] = row * RB + v_swz_slot<D>(row, dcol >> 4) * 32 + (dcol & 15) * 2;
             }
+            if constexpr (NB3) {  // the V buffers start NB tiles into LDS; opaque, or the compiler folds it into the immediates
+                int shift = NB * TILE_BYTES;
+                asm volatile("" : "+v"(shift));
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) voff[dt] += shift;
+            }
         }
 
         // All helper lambdas below are force-inlined: they capture the register arrays (o, s,
@@ -362,12 +376,12 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
                 if (jk >= 0) {
 #pragma unroll
                     for (int i = 0; i < LD_PER_THREAD; ++i)
-                        issue_piece(nt_c, W, Kh, goffK0, wave, ktk, smem_b + kbuf * 2 * TILE_BYTES, i, kst[LDP == 0 ? i : 0]);
+                        issue_piece(nt_c, W, Kh, goffK0, wave, ktk, smem_b + k_off(kbuf), i, kst[LDP == 0 ? i : 0]);
                 }
                 if (jv >= 0) {
 #pragma unroll
                     for (int i = 0; i < LD_PER_THREAD; ++i)
-                        issue_piece(nt_c, W, Vh, goffV0, wave, ktv, smem_b + vbuf * 2 * TILE_BYTES + TILE_BYTES, i, vst[LDP == 0 ? i : 0]);
+                        issue_piece(nt_c, W, Vh, goffV0, wave, ktv, smem_b + v_off(vbuf), i, vst[LDP == 0 ? i : 0]);
                 }
             };
             if (whole) pieces(std::true_type{});
@@ -410,8 +424,8 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
             if constexpr (LDP == 1) {
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             } else {
-                char* kb = smem_b + kbuf * 2 * TILE_BYTES;
-                char* vb = smem_b + vbuf * 2 * TILE_BYTES + TILE_BYTES;
+                char* kb = smem_b + k_off(kbuf);
+                char* vb = smem_b + v_off(vbuf);
 #pragma unroll
                 for (int i = 0; i < LD_PER_THREAD; ++i) {
                     *reinterpret_cast<u32x4*>(kb + (i * NT + tid) * 16) = kst[i];
@@ -432,8 +446,8 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
             constexpr bool HAS_PV = decltype(has_pv_c)::value, HAS_QK = decltype(has_qk_c)::value;
             constexpr int VB = decltype(vbuf_c)::value, KB = decltype(kbuf_c)::value;
             constexpr int N0 = HAS_PV ? NVF : 0, NS = N0 + (HAS_QK ? NKF : 0);
-            const char* vb = smem_b + VB * 2 * TILE_BYTES + TILE_BYTES;
-            const char* kb = smem_b + KB * 2 * TILE_BYTES;
+            const char* vb = smem_b + v_rel(VB);
+            const char* kb = smem_b + k_off(KB);
             auto read_frag = [&](int i) __attribute__((always_inline)) -> u32x4 {
                 if (i < N0) {  // V fragment i = (kt*2 + t)*DT + dt
                     const int dt = i % DT, t = (i / DT) & 1, kt = i / (2 * DT);
@@ -1083,10 +1097,65 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
             __syncthreads();
             if constexpr (QSTAGE) read_q();
             mfma_stream(no, yes, c0, c0, pk, s);
+            if constexpr (NB3) issue_tiles(2, 2, 1, 1);
             softmax_first_tile(s, pk);
+            if constexpr (NB3) land_loads(0, 0);
             __syncthreads();  // every wave has read K(0) before K(2) overwrites it
 
-            if constexpr (PIPE == 1) {
+            if constexpr (NB3) {
+                // Three buffers: in period j (from one barrier to the next; group A runs M_j then V_j,
+                // group B V_(j-1) then M_j) the M clusters read K(j+1) in K buffer (j+1)%3 and V(j) in V
+                // buffer j%3, and the loads bring K(j+3) into K buffer j%3 and V(j+2) into V buffer
+                // (j+2)%3, both last read in period j-1 and first read in period j+2.  The only thing
+                // a barrier still has to separate is one period from the next: one barrier per tile
+                // instead of two, and the two waves of a SIMD keep their alternation by themselves
+                // (each does one M and one V cluster per period, in opposite order).  K(2) and V(1),
+                // which periods 0 and 1 read, were requested behind the S(0) stream.
+                static_assert(LDP == 1, "three buffers: tiles straight to LDS");
+                auto period_loads = [&](int j) __attribute__((always_inline)) { issue_tiles(j + 3, j % 3, j + 2, (j + 2) % 3); };
+                auto cluster_m3 = [&](auto r_c, int j) __attribute__((always_inline)) {  // r = j % 3
+                    constexpr int R = decltype(r_c)::value;
+                    constexpr std::integral_constant<int, (R + 1) % 3> kbuf{};
+                    if (tile_active(j)) mfma_stream(yes, yes, r_c, kbuf, pk, s);
+                };
+                auto cluster_v = [&](int j) __attribute__((always_inline)) {
+                    if (tile_active(j + 1)) softmax_tile(s, pk, (j + 1) * BN);
+                };
+                constexpr std::integral_constant<int, 2> c2{};
+                // (one loop per group: a branch on the group inside one loop would give the accumulators
+                // two code paths and the register allocator a reason to move them)
+                if (!grp_b) {
+                    auto period = [&](auto r_c, int j) __attribute__((always_inline)) {
+                        cluster_m3(r_c, j);
+                        period_loads(j);
+                        cluster_v(j);
+                        land_loads(0, 0);
+                        __syncthreads();
+                    };
+                    for (int j = 0; j < nkt; j += 3) {
+                        period(c0, j);
+                        if (j + 1 >= nkt) break;
+                        period(c1, j + 1);
+                        if (j + 2 >= nkt) break;
+                        period(c2, j + 2);
+                    }
+                } else {
+                    auto period = [&](auto r_c, int j) __attribute__((always_inline)) {
+                        period_loads(j);
+                        if (j > 0) cluster_v(j - 1);
+                        land_loads(0, 0);
+                        cluster_m3(r_c, j);
+                        __syncthreads();
+                    };
+                    for (int j = 0; j < nkt; j += 3) {
+                        period(c0, j);
+                        if (j + 1 >= nkt) break;
+                        period(c1, j + 1);
+                        if (j + 2 >= nkt) break;
+                        period(c2, j + 2);
+                    }
+                }
+            } else if constexpr (PIPE == 1) {
                 // Every wave issues its share of a tile at the start of one of its V clusters
                 // (group B in slot 2j, group A in slot 2j+1).
                 auto slot_loads = [&](int j) __attribute__((always_inline)) {  // the loads of slot 2j; buffer indices are runtime here
