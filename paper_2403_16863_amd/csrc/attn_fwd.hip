@@ -485,10 +485,13 @@ int attn_variant_from_coords(const int* coords) {
 }
 
 // Defaults chosen from the measured search over the variant table on MI355X: the
-// two-cluster ping-pong order (256-row query tiles) wins for head_dim 128 and for long
-// sequences with head_dim 64; short sequences with head_dim 64 have too few such tiles to
-// go round and run the free-running order on 128-row tiles.  (Ids index kVariants.)
-constexpr int kDefaultD128 = 11;
+// two-cluster ping-pong order (256-row query tiles) wins for head_dim 128, in its form with
+// three buffers, one barrier per tile and an LDS prefetch distance of 2 (about 1 % ahead of the
+// two-buffer form, variant 11, on both long workloads, every time the two were timed alternately);
+// long sequences with head_dim 64 run three free-running workgroups per compute unit, short ones
+// have too few 256-row tiles to go round and run the free-running order on 128-row tiles.
+// (Ids index kVariants.)
+constexpr int kDefaultD128 = 36;
 constexpr int kDefaultD64Long = 18;
 constexpr int kDefaultD64Short = 3;
 
