@@ -246,6 +246,16 @@ def ceilings(A, achieved):
         tf, ghz = A.attn_mix_ceiling(mode)
         mix[name] = {"TFLOP/s": tf, "core_GHz": ghz}
     mix["frac_of_full_mix_rate"] = achieved / mix["mfma_lds_reads_and_softmax_arithmetic"]["TFLOP/s"]
+    # the same mix in the ping-pong form of the default kernels (one wave of a SIMD in an MFMA cluster, the
+    # other in a vector cluster): what that structure costs before any tile load, mask or item boundary
+    import torch
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    for mode, name in ((3, "pingpong_form_two_barriers_per_tile"), (4, "pingpong_form_one_barrier_per_tile")):
+        tf, ghz = A.attn_mix_ceiling(mode, 40000)
+        mix[name] = {"TFLOP/s": tf, "core_GHz": ghz,
+                     "clocks_per_tile": (ghz * 1e9 * 32 * 32768.0 * 8 * cus / (tf * 1e12)) if tf > 0 else None,
+                     "mfma_clocks_per_tile": 2048}
+    mix["frac_of_pingpong_form_rate"] = achieved / mix["pingpong_form_one_barrier_per_tile"]["TFLOP/s"]
     mfma["loop_body_mix_kernel"] = mix
     valu = {"mix": "per score element 1 fma + 1 exp2 + 1 add + 1/2 conversion to 16 bit, from registers, no packed fp32",
             "note": "an element stands for 4*d flops of the two contractions: implied ceilings below"}

@@ -213,7 +213,11 @@ int attn_mfma_ceiling(int random_operands, int iters, void* stream, unsigned lon
  * softmax.  The kernel issues that and nothing else (random operands, fragments read four steps
  * ahead, two waves per SIMD, `iters` rounds of 16 MFMAs per wave; no tile loads, barriers, masks
  * or item boundaries; launched twice, the second launch is the one timed): mode 0 = MFMAs only,
- * 1 = MFMAs and LDS reads, 2 = the whole mix.  The
+ * 1 = MFMAs and LDS reads, 2 = the whole mix, every wave issuing all of it interleaved.  Modes 3
+ * and 4 run the whole mix in the ping-pong form of the default kernels instead: per round a wave
+ * runs one cluster of 32 MFMAs with their LDS reads and one cluster of the softmax's vector
+ * instructions for 32 scores per lane, the two waves of a SIMD in opposite order, with two
+ * workgroup barriers per round (mode 3) or one (mode 4); `iters` rounds of 32 MFMAs per wave.  The
  * device runs it at its power limit, as it runs the attention kernel, so *tflops (host) is what
  * the loop body can reach there; *core_ghz (host) is the clock during the run (0 if the clock
  * counters could not be read).  counters: device memory, 3 x 8 bytes, written by the kernel

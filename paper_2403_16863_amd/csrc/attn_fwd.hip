@@ -392,6 +392,104 @@ __global__ __launch_bounds__(512) void mix_ceiling_kernel(unsigned long long* co
     if (sum == 1.2345e-30f || keep == 0x12345678u) counters[2] = 1;  // keeps the results alive
 }
 
+// ---- measurement aid: the same work in the ping-pong form and nothing else.  Eight waves per workgroup,
+// two per SIMD; per "tile" a wave runs one MFMA cluster (32 MFMAs, each with one 1 KB fragment read
+// from LDS two steps ahead, the first 16 on four accumulators, the other 16 on two, like PV and S) and
+// one vector cluster (per lane 32 multiply-adds, 32 exp2, 32 additions, 16 conversions, in the pinned
+// order of the attention kernel), the waves 4..7 in the opposite order, with BARRIERS workgroup
+// barriers per tile (2: after every cluster; 1: after every tile).  No tile loads, masks, item
+// boundaries or epilogues: what is left is the structure itself, one wave of a SIMD feeding the
+// matrix pipe while the other one issues vector instructions.
+template <int BARRIERS>
+__global__ __launch_bounds__(512) void pingpong_ceiling_kernel(unsigned long long* counters, int iters) {
+    typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x16 __attribute__((ext_vector_type(16)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    __shared__ u32x4 lds[4096];  // 64 KB of random 16-bit patterns
+    unsigned st = (blockIdx.x * 512 + threadIdx.x) * 2654435761u + 12345u;
+    auto rnd = [&]() {  // random sign and mantissa, exponent 126 or 127: magnitudes in [0.5, 2)
+        st = st * 1664525u + 1013904223u;
+        return (st & 0x807f807fu) | 0x3f003f00u | ((st >> 3) & 0x00800080u);
+    };
+    for (int i = threadIdx.x; i < 4096; i += 512) lds[i] = u32x4{rnd(), rnd(), rnd(), rnd()};
+    __syncthreads();
+    u32x4 b[4];
+    for (int n = 0; n < 4; ++n) b[n] = u32x4{rnd(), rnd(), rnd(), rnd()};
+    f32x16 acc[6];
+    for (int n = 0; n < 6; ++n)
+        for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
+    float x[32];
+    for (int i = 0; i < 32; ++i) x[i] = -0.01f * (float)((st >> (i & 7)) & 255);
+    float rs0 = 0.f, rs1 = 0.f;
+    unsigned keep = 0;
+    const char* lb = reinterpret_cast<const char*>(lds) + ((threadIdx.x * 16) & 0x3ff0);
+    const bool grp_b = threadIdx.x >= 256;
+    auto cluster_m = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_s_setprio(2);
+        u32x4 ring[2];
+        ring[0] = *reinterpret_cast<const u32x4*>(lb);
+        ring[1] = *reinterpret_cast<const u32x4*>(lb + 16384);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int n = 0; n < 32; ++n) {
+            const int a = n < 16 ? (n & 3) : 4 + (n & 1);
+            acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ring[n & 1]), __builtin_bit_cast(bf16x8, b[n & 3]), acc[a], 0, 0, 0);
+            if (n + 2 < 32) ring[n & 1] = *reinterpret_cast<const u32x4*>(lb + ((n + 2) & 3) * 16384);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_s_setprio(0);
+    };
+    auto cluster_v = [&]() __attribute__((always_inline)) {
+        float xa = 0.f, xb = 0.f, ea = 0.f, eb = 0.f;
+#pragma unroll
+        for (int i = 0; i < 18; ++i) {  // pair i enters, pair i-1 in exp2, pair i-2 leaves
+            float na = 0.f, nb = 0.f, fa = 0.f, fb = 0.f;
+            if (i >= 1 && i <= 16) { fa = __builtin_amdgcn_exp2f(xa); __builtin_amdgcn_sched_barrier(0); }
+            if (i < 16) { na = __builtin_fmaf(x[2 * i], 0.127517f, -0.25f); __builtin_amdgcn_sched_barrier(0); }
+            if (i >= 2) { rs0 += ea; __builtin_amdgcn_sched_barrier(0); }
+            if (i >= 2) {
+                unsigned pk = __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{ea, eb}, bf16x2));
+                asm volatile("" : "+v"(pk));
+                keep ^= pk;
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (i >= 1 && i <= 16) { fb = __builtin_amdgcn_exp2f(xb); __builtin_amdgcn_sched_barrier(0); }
+            if (i < 16) { nb = __builtin_fmaf(x[2 * i + 1], 0.127517f, -0.25f); __builtin_amdgcn_sched_barrier(0); }
+            if (i >= 2) { rs1 += eb; __builtin_amdgcn_sched_barrier(0); }
+            xa = na; xb = nb; ea = fa; eb = fb;
+        }
+#pragma unroll
+        for (int i = 0; i < 32; ++i) asm volatile("" : "+v"(x[i]));
+    };
+    const unsigned long long c0 = clock64(), r0 = wall_clock64();
+    if (!grp_b) {
+        for (int it = 0; it < iters; ++it) {
+            cluster_m();
+            if constexpr (BARRIERS == 2) __syncthreads();
+            cluster_v();
+            __syncthreads();
+        }
+    } else {
+        for (int it = 0; it < iters; ++it) {
+            cluster_v();
+            if constexpr (BARRIERS == 2) __syncthreads();
+            cluster_m();
+            __syncthreads();
+        }
+    }
+    const unsigned long long c1 = clock64(), r1 = wall_clock64();
+    float sum = rs0 + rs1;
+    for (int n = 0; n < 6; ++n)
+        for (int v = 0; v < 16; ++v) sum += acc[n][v];
+    if (blockIdx.x == 7 && threadIdx.x == 0) {
+        counters[0] = c1 - c0;  // core clock cycles
+        counters[1] = r1 - r0;  // ticks of the constant 100 MHz clock
+    }
+    if (sum == 1.2345e-30f || keep == 0x12345678u) counters[2] = 1;  // keeps the results alive
+}
+
 // ---- measurement aid: what the vector ALU sustains on the softmax's own instruction mix.  Per
 // score element the one-pass softmax issues one fma (scale and shift), one exp2, one add (row sum)
 // and half a conversion (two probabilities per packed 16-bit pair); this kernel issues exactly
@@ -686,7 +784,7 @@ int attn_mfma_ceiling(int random_operands, int iters, void* stream, unsigned lon
 }
 
 int attn_mix_ceiling(int mode, int iters, void* stream, unsigned long long* counters, double* tflops, double* core_ghz) {
-    if (mode < 0 || mode > 2 || iters < 1 || !counters || !tflops || !core_ghz) return ATTN_EINVAL;
+    if (mode < 0 || mode > 4 || iters < 1 || !counters || !tflops || !core_ghz) return ATTN_EINVAL;
     hipStream_t s = (hipStream_t)stream;
     const int blocks = cu_count();  // one workgroup of 8 waves per CU: two waves per SIMD
     hipEvent_t e0, e1;
@@ -696,7 +794,8 @@ int attn_mix_ceiling(int mode, int iters, void* stream, unsigned long long* coun
     float ms = 0.f;
     unsigned long long h[2] = {0, 0};
     void* args[] = {&counters, &iters};
-    const void* kernels[3] = {(const void*)mix_ceiling_kernel<0>, (const void*)mix_ceiling_kernel<1>, (const void*)mix_ceiling_kernel<2>};
+    const void* kernels[5] = {(const void*)mix_ceiling_kernel<0>, (const void*)mix_ceiling_kernel<1>, (const void*)mix_ceiling_kernel<2>,
+                              (const void*)pingpong_ceiling_kernel<2>, (const void*)pingpong_ceiling_kernel<1>};
     // one untimed launch first: from idle the device takes tens of milliseconds to reach the clock it sustains
     if (hipLaunchKernel(kernels[mode], dim3(blocks), dim3(512), args, 0, s) != hipSuccess ||
         hipEventRecord(e0, s) != hipSuccess ||
@@ -708,7 +807,7 @@ int attn_mix_ceiling(int mode, int iters, void* stream, unsigned long long* coun
     hipEventDestroy(e0);
     hipEventDestroy(e1);
     if (rc != ATTN_OK) return rc;
-    *tflops = (double)blocks * 8 * (double)iters * 16 * 32768.0 / ((double)ms * 1e-3) / 1e12;
+    *tflops = (double)blocks * 8 * (double)iters * (mode >= 3 ? 32 : 16) * 32768.0 / ((double)ms * 1e-3) / 1e12;
     *core_ghz = h[1] ? (double)h[0] / ((double)h[1] * 10.0) : 0.0;
     return ATTN_OK;
 }
