@@ -222,7 +222,7 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
     // (Also for the free-running order at d = 64, where the staging area fits next to the tiles
     // of three workgroups per compute unit; at d = 128 two such workgroups would need 192 KB.)
     constexpr bool QSTAGE = LDP == 1 && QB == 1 && (PIPE == 1 || (PIPE == 0 && D == 64));
-    __shared__ __attribute__((aligned(256))) u32x4 smem[2 * NB * TILE_CHUNKS + (QSTAGE ? BM * CPR : 0)];  // K0 V0 K1 V1, Q
+    __shared__ __attribute__((aligned(256))) u32x4 smem[2 * NB * TILE_CHUNKS + (QSTAGE ? BM * CPR : 0)];  // K0 V0 K1 V1 (three buffers: K0 K1 K2 V0 V1 V2), then the Q staging area
     char* const smem_b = reinterpret_cast<char*>(smem);
 
     auto k_off = [](int b) { return NB3 ? b * TILE_BYTES : b * 2 * TILE_BYTES; };                       // K buffer b, bytes from the start of LDS
