@@ -76,6 +76,10 @@ enum {
  * (binary16) and 3.8 (bfloat16) in the worst case (a row that puts all its weight on large
  * values of one sign); for larger outputs the bound is the relative one.
  * lse is accurate to about 1e-6 relative (fp32 sums of unrounded probabilities).
+ * Overflow: the exact O never exceeds max |V| (a convex combination), but the computed one may
+ * by the error above; in binary16 a finite result beyond the largest finite value (65504) is
+ * stored as +-65504, not as infinity (infinities and NaN that come from the inputs pass
+ * unchanged).  bfloat16 outputs cannot get there within the V magnitude limit below.
  * V magnitude: the one-pass method keeps the un-normalised sum of p*v in fp32, with p up to
  * 2^8 before the reference maximum is raised, so |V| * N * 2^8 must stay below the fp32 range
  * (3.4e38): every finite binary16 V qualifies, bfloat16 V must stay below about 1e38 / (256 N).

@@ -239,6 +239,13 @@ __global__ __launch_bounds__(KN::NW * 64, KN::OCC) void attn_fwd_kernel(const Pa
         return schedule_item((int)gridDim.x, (int)blockIdx.x, p.BH, p.nqt, round, bh, qt);
     };
     const int N = p.N;
+    // binary16 only: a finite result above the largest finite binary16 value is stored as that
+    // value, not as infinity (mode bit FP16_OVFL; true infinities and NaN pass unchanged).  The
+    // exact O is a convex combination of V values, so it never exceeds max |V|; the computed one
+    // can, by a rounding error: P is rounded to 16 bits before the second contraction while the
+    // row sum keeps the unrounded values, and with V at the largest finite value a few
+    // probabilities rounded upwards put O half a unit in the last place above it.
+    if constexpr (std::is_same_v<T, F16>) asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 23, 1), 1");
     for (int round = 0;; ++round) {
         int bh, qt;
         if (!item_of_round(round, bh, qt)) break;

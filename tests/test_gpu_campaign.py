@@ -118,3 +118,36 @@ def test_gemm_campaign_against_oracle():
             print(f"gemm campaign: {n + 1} samples passed, {time.time() - t0:.0f} s", flush=True)
     print(f"gemm campaign: {samples} samples passed in {time.time() - t0:.1f} s; worst error as a fraction of the "
           f"tolerance: {worst:.3f}", flush=True)
+
+
+@pytest.mark.gpu
+def test_largest_finite_binary16_v_never_overflows():
+    """O is a convex combination of V values, so with V at the largest finite binary16 value the
+    exact output stays finite; P rounded upwards may put the computed one half a unit in the last
+    place above it, which must be stored as the largest finite value, not as infinity.  First the
+    sample of a random campaign that found this (seed 141421, sample 69835), on every variant; then
+    the sharpest form: every V element equal to +65504 (or -65504), so every output element is
+    exactly that value and any net upward rounding of P would overflow."""
+    import paper_2403_16863_amd as A
+    big = 65504.0
+    scale = float(np.float32(1.0) / np.sqrt(np.float32(64)))
+    qb, kb, vb = I.make_adversarial("max_finite_v", 1, 3, 256, 64, I.F16, 598254998)
+    O_ref, l_ref, _ = ref.attn_ref(qb, kb, vb, True, scale, I.F16)
+    variants = [None] + [v for v in range(A.attn_num_variants()) if A.attn_variant_supported(v, 64, I.F16, True)]
+    for variant in variants:
+        O, l = run_gpu(qb, kb, vb, True, scale, I.F16, variant=variant)
+        assert np.isfinite(O).all() and np.isfinite(l).all(), f"variant {variant}"
+        assert float(np.max(np.abs(O - O_ref))) / big <= O_TOL[I.F16], f"variant {variant}"
+        assert float(np.max(np.abs(l - l_ref) / np.maximum(1.0, np.abs(l_ref)))) <= LSE_RTOL, f"variant {variant}"
+    for d in (64, 128):
+        for causal in (True, False):
+            for sign in (1.0, -1.0):
+                w = I.Workload("c", 2, 4, 193, d, causal, I.F16)
+                qb, kb, vb = I.make_qkv(w, 11 + d)
+                vb = I.f32_to_bits(np.full((2, 4, 193, d), sign * big, dtype=np.float32), I.F16)
+                sc = float(np.float32(1.0) / np.sqrt(np.float32(d)))
+                for variant in [None] + [v for v in range(A.attn_num_variants()) if A.attn_variant_supported(v, d, I.F16, causal)]:
+                    O, _ = run_gpu(qb, kb, vb, causal, sc, I.F16, variant=variant)
+                    assert np.isfinite(O).all(), f"d {d} causal {causal} sign {sign} variant {variant}"
+                    # 65504 or the binary16 value below it (65472)
+                    assert float(np.max(np.abs(O - sign * big))) <= 32.0, f"d {d} causal {causal} sign {sign} variant {variant}"
