@@ -76,6 +76,9 @@ enum {
  * (binary16) and 3.8 (bfloat16) in the worst case (a row that puts all its weight on large
  * values of one sign); for larger outputs the bound is the relative one.
  * lse is accurate to about 1e-6 relative (fp32 sums of unrounded probabilities).
+ * Score magnitude: the scaled scores x_j are formed in fp32 (MFMA accumulation, then one fused
+ * multiply-add against the reference maximum), so a probability carries a relative error of about
+ * |x_j| * 2^-22 on top of the above: nothing up to |x| ~ 1e4, a per cent at |x| ~ 1e5.
  * Overflow: the exact O never exceeds max |V| (a convex combination), but the computed one may
  * by the error above; in binary16 a finite result beyond the largest finite value (65504) is
  * stored as +-65504, not as infinity (infinities and NaN that come from the inputs pass
