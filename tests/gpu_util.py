@@ -8,6 +8,17 @@ from paper_2403_16863_amd import inputs as I
 # |d lse| <= 1e-3 * max(1, |lse|).
 O_TOL = {I.F16: 1e-2, I.BF16: 3e-2}
 LSE_RTOL = 1e-3
+# Half-unit roundoff of the 16-bit types.  For inputs beyond unit scale the error of O is bounded
+# relative to the largest |V|: u * sum_j p_j |v_j| from rounding P to 16 bits, u * |O| from the
+# final rounding, fp32 terms far below both, i.e. at most about 2 u max|V|.  The absolute
+# tolerances above are that bound at max|V| = 10 (binary16) and 3.8 (bfloat16).
+U = {I.F16: 2.0 ** -11, I.BF16: 2.0 ** -8}
+
+
+def o_tol(dtype, vmax):
+    """Tolerance on max |dO| for inputs whose largest |V| is vmax: the absolute one of the target
+    statement up to the V magnitude where the error bound reaches it, the bound beyond."""
+    return max(O_TOL[dtype], 2.1 * U[dtype] * float(vmax))
 
 
 def torch_dtype(dtype):

@@ -5,6 +5,9 @@ number of samples comes from ATTN_CAMPAIGN_SAMPLES (default 120: a few seconds).
 script for a long campaign:  ATTN_CAMPAIGN_SAMPLES=5000 python -m pytest tests/test_gpu_campaign.py -m gpu -s
 With ATTN_CAMPAIGN_ALL_VARIANTS=1 every sample also draws one of the schedule variants built for
 its head dimension, instead of the library default (by default every fourth sample does).
+Tolerance on O: the absolute one of the target statement (1e-2 binary16, 3e-2 bfloat16) as long as
+the largest |V| of the sample is inside the range for which the accuracy bound 2 u max|V| stays
+below it (10 and 3.8), that bound beyond (tests.gpu_util.o_tol); lse: 1e-3 relative.
 """
 import os
 import random
@@ -15,7 +18,7 @@ import pytest
 
 from oracle import ref
 from paper_2403_16863_amd import inputs as I
-from tests.gpu_util import O_TOL, LSE_RTOL, run_gpu
+from tests.gpu_util import O_TOL, LSE_RTOL, o_tol, run_gpu
 
 FAMILIES = ("normal", "normal", "normal", "wide", "peaked", "equal_scores", "large_negative",
             "single_v_row", "signed_zero", "max_finite_v", "rising_scores")
@@ -40,7 +43,7 @@ def draw(rng):
 def test_campaign_against_oracle():
     samples = int(os.environ.get("ATTN_CAMPAIGN_SAMPLES", "120"))
     rng = random.Random(int(os.environ.get("ATTN_CAMPAIGN_SEED", "2024")))
-    worst_o, worst_l, t0 = 0.0, 0.0, time.time()
+    worst_o, worst_l, worst_abs, t0 = 0.0, 0.0, 0.0, time.time()
     worst_what = ""
     by_family = {}
     trace = os.environ.get("ATTN_CAMPAIGN_TRACE")  # file that names the sample in flight, for a run that dies
@@ -67,21 +70,24 @@ def test_campaign_against_oracle():
             variant = vrng.choice([v for v in range(A.attn_num_variants()) if A.attn_variant_supported(v, d, dtype, causal)])
         by_variant[variant] = by_variant.get(variant, 0) + 1
         O, l = run_gpu(qb, kb, vb, causal, scale, dtype, variant=variant)
-        out_scale = max(1.0, float(np.abs(I.bits_to_f64(vb, dtype)).max())) if fam == "max_finite_v" else 1.0
+        tol = o_tol(dtype, np.abs(I.bits_to_f64(vb, dtype)).max())  # the absolute tolerance, or 2 u max|V| where that is larger
         what = f"sample {n}: B{B} H{H} N{N} d{d} dtype{dtype} causal{causal} {fam} seed{seed} variant{variant}"
         assert np.isfinite(O).all() and np.isfinite(l).all(), what
-        eo = float(np.max(np.abs(O - O_ref))) / out_scale
+        eo = float(np.max(np.abs(O - O_ref)))
         el = float(np.max(np.abs(l - l_ref) / np.maximum(1.0, np.abs(l_ref))))
-        assert eo <= O_TOL[dtype], f"{what}: max|dO| = {eo:.3e}"
+        assert eo <= tol, f"{what}: max|dO| = {eo:.3e} > {tol:.3e}"
         assert el <= LSE_RTOL, f"{what}: lse error {el:.3e}"
-        if eo / O_TOL[dtype] > worst_o:
-            worst_o, worst_what = eo / O_TOL[dtype], what
+        if eo / tol > worst_o:
+            worst_o, worst_what = eo / tol, what
+        if fam != "max_finite_v":
+            worst_abs = max(worst_abs, eo / O_TOL[dtype])
         worst_l = max(worst_l, el / LSE_RTOL)
         by_family[fam] = by_family.get(fam, 0) + 1
         if (n + 1) % 250 == 0:
             print(f"campaign: {n + 1} samples passed, {time.time() - t0:.0f} s", flush=True)
     print(f"campaign: {samples} samples passed in {time.time() - t0:.1f} s; worst error as a fraction of the "
-          f"tolerance: O {worst_o:.3f} ({worst_what}), lse {worst_l:.3f}; families {by_family}; "
+          f"tolerance: O {worst_o:.3f} ({worst_what}), lse {worst_l:.3f}; worst O error over the fixed absolute "
+          f"tolerance, all families but max_finite_v: {worst_abs:.3f}; families {by_family}; "
           f"variants (None = library default) {dict(sorted(by_variant.items(), key=lambda kv: -1 if kv[0] is None else kv[0]))}", flush=True)
 
 
@@ -137,7 +143,7 @@ def test_largest_finite_binary16_v_never_overflows():
     for variant in variants:
         O, l = run_gpu(qb, kb, vb, True, scale, I.F16, variant=variant)
         assert np.isfinite(O).all() and np.isfinite(l).all(), f"variant {variant}"
-        assert float(np.max(np.abs(O - O_ref))) / big <= O_TOL[I.F16], f"variant {variant}"
+        assert float(np.max(np.abs(O - O_ref))) <= o_tol(I.F16, big), f"variant {variant}"
         assert float(np.max(np.abs(l - l_ref) / np.maximum(1.0, np.abs(l_ref)))) <= LSE_RTOL, f"variant {variant}"
     for d in (64, 128):
         for causal in (True, False):
